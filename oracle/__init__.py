@@ -1,0 +1,21 @@
+"""fp64 CPU oracle for the tile-based denoising hot path (TEST INFRASTRUCTURE ONLY).
+
+This package is the slow, plain definition of what the HIP kernels compute.  It
+shares no code with the HIP path and must never be imported by the product
+package: only tests, the smoke check and the CPU-baseline leg of the benchmark
+may call it.
+"""
+from .tile_oracle import (  # noqa: F401
+    tile_origin,
+    slice_tile,
+    softmax_rows,
+    attention_rows,
+    attention,
+    tile_attention,
+    ramp_weight,
+    blend,
+    gate_score,
+    cache_gate,
+    StepState,
+    denoise_step_tiled,
+)
