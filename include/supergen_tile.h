@@ -1,0 +1,171 @@
+/*
+ * supergen_tile.h - C ABI of the tile-based denoising hot path on one MI355X (gfx950).
+ *
+ * The library computes, for a latent canvas of T x H x W tokens that is partitioned into
+ * overlapping tiles along H and W only (every tile keeps all T frames; paper Section 4.3,
+ * Algorithm 1 stage 2: PartitionTiles / SliceTile):
+ *
+ *   sg_tile_attention       3D full self-attention over one tile's tokens (paper Section 2.1
+ *                           "full attention"; Section 3: no Q/K/V exchange across tiles)
+ *   sg_tile_blend           Fuse: merge all tile outputs into the full canvas (Algorithm 1
+ *                           "Fuse"; Section 4.3; Tile Fuser of Section 5)
+ *   sg_cache_gate           per-tile cache decision from the relative L1 change of the tile
+ *                           input (Equation 3) against a threshold (Equation 8)
+ *   sg_denoise_step_tiled   one stage-2 step: gate -> attention on the tiles to recompute ->
+ *                           cache refresh -> Fuse (Algorithm 1 loop body; Section 5.1 pipeline)
+ *
+ * Conventions shared by every entry point
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *     ordinary process memory.  Every buffer is owned by the caller; the library allocates
+ *     nothing and keeps no state between calls (scratch comes from the caller's workspace).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it and the calls return without waiting; no host readback takes place.
+ *   - Inputs are never written.  Outputs must not alias inputs.
+ *   - Argument checks run on the host before anything is launched; a failed check launches
+ *     nothing.  Return value: SG_OK (0) or a negative sg_status.
+ *   - Element types: SG_F32 (IEEE binary32) or SG_BF16 (bfloat16, round-to-nearest-even on
+ *     store).  bf16 problems multiply in bf16 on the matrix cores and accumulate in fp32;
+ *     f32 problems compute in fp32 throughout.
+ *   - Token order: a canvas token (t, y, x) has linear index n = (t*H + y)*W + x; element c of
+ *     head a of token n of a canvas tensor lives at
+ *         base + a*grid_stride_head + n*grid_stride_token + c          (in elements),
+ *     so [heads][T][H][W][d] (grid_stride_token = d, grid_stride_head = T*H*W*d) and
+ *     [T][H][W][heads][d] (grid_stride_token = heads*d, grid_stride_head = d) are both
+ *     expressible.  Canvas base pointers must be 16-byte aligned and both strides multiples of
+ *     8 elements.
+ *   - A packed tile is [heads][T][tile_h][tile_w][d], contiguous; tile tokens are ordered
+ *     (t, i, j) with j fastest.  Tile (tile_row, tile_col) has its top-left token at canvas
+ *     row tile_row*stride_h, column tile_col*stride_w; tiles are listed row-major.
+ */
+#ifndef SUPERGEN_TILE_H
+#define SUPERGEN_TILE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SG_F32 = 0, SG_BF16 = 1 } sg_dtype;
+
+typedef enum {
+  SG_OK = 0,
+  SG_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, tiles not covering the canvas, ... */
+  SG_ERR_UNSUPPORTED = -2, /* a valid problem this build has no kernel for (head_dim, dtype, tile count) */
+  SG_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than sg_workspace_bytes() */
+  SG_ERR_HIP = -4          /* a HIP call failed; see sg_last_hip_error() */
+} sg_status;
+
+/* Largest number of tiles per canvas (their pointers travel as kernel arguments). */
+#define SG_MAX_TILES 256
+
+/* Problem statement: canvas, tiling, attention shape.  Plain data, passed by pointer (host). */
+typedef struct sg_problem {
+  int32_t T, H, W;                  /* canvas size in tokens                                   */
+  int32_t tile_h, tile_w;           /* tile size in tokens (a tile spans all T)                */
+  int32_t stride_h, stride_w;       /* spacing of tile origins; overlap = tile - stride >= 0   */
+  int32_t n_tile_rows, n_tile_cols; /* (n-1)*stride + tile must equal H (resp. W)              */
+  int32_t heads, head_dim;          /* head_dim: 64 or 128                                     */
+  int32_t dtype;                    /* sg_dtype of every tensor of the problem                 */
+  float scale;                      /* softmax scale applied to Q.K^T, > 0 (1/sqrt(head_dim))  */
+  int64_t grid_stride_token;        /* canvas tensors: elements between consecutive tokens     */
+  int64_t grid_stride_head;         /* canvas tensors: elements between consecutive heads      */
+} sg_problem;
+
+/* Library version, "major.minor". */
+const char* sg_version(void);
+/* Static text for a status code. */
+const char* sg_status_string(int status);
+/* Numeric hipError_t of the last failed HIP call made by the calling thread (0 if none). */
+int sg_last_hip_error(void);
+
+/* Checks a problem statement (host only, launches nothing). */
+int sg_problem_validate(const sg_problem* p);
+
+/* Bytes of device scratch that sg_cache_gate / sg_denoise_step_tiled need for `n_tiles` tiles.
+ * The workspace must be 256-byte aligned device memory; its contents need no initialisation
+ * and it may be reused by the next call on the same stream. */
+int sg_workspace_bytes(int32_t n_tiles, size_t* out_bytes);
+
+/*
+ * Tile attention (paper Sections 2.1 and 3; Algorithm 1 "SliceTile" + the self-attention of
+ * "Model.DiT").  For tile (tile_row, tile_col), per head a and tile token n:
+ *     O[a][n][:] = sum_m softmax_m( scale * <Q[a][n], K[a][m]> ) * V[a][m][:]
+ * over all N = T*tile_h*tile_w tokens m of the same tile: bidirectional, no mask, no bias.
+ *   q, k, v   device, canvas tensors (layout above); the tile is read in place, never copied
+ *   out_tile  device, packed tile [heads][T][tile_h][tile_w][head_dim], 16-byte aligned
+ * A packed tile is attended by describing it as a canvas that is one tile (H = tile_h,
+ * W = tile_w, 1 x 1 tiles).
+ */
+int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const void* v,
+                      int32_t tile_row, int32_t tile_col, void* out_tile, void* stream);
+
+/*
+ * Fuse / overlap blend (Algorithm 1 "Fuse"; Section 4.3).  For every canvas token g, head and
+ * channel:
+ *     out[g] = sum_{tiles covering g} w(g) * O_tile(g)  /  sum_{tiles covering g} w(g)
+ *     w = w_h(i) * w_w(j),  w_axis(i) = min(1, (i+1)/(o+1), (L-i)/(o+1)),
+ * i, j = the token's row/column inside the tile, L = tile length and o = L - stride along that
+ * axis; the T axis carries weight 1.  With o = 0 this is the paper's non-overlapping placement.
+ * Weights and sums are fp32; one rounding to the output type.
+ *   tile_out  host array of n_tile_rows*n_tile_cols device pointers to packed tiles (row-major)
+ *   grid_out  device, canvas tensor with the problem's strides
+ */
+int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_out, void* stream);
+
+/*
+ * Cache gate (Equation 3 relative L1 with the cached tensor as denominator; Equation 8:
+ * strictly below the threshold reuses, at or above recomputes).  Per tile i:
+ *     score[i]     = sum|x_cur[i] - x_cached[i]| / sum|x_cached[i]|      (+inf if the sum is 0)
+ *     recompute[i] = !has_cache[i] || score[i] >= threshold
+ * A tile without a cache gets score +inf and its buffers are not read.
+ *   x_cur, x_cached  host arrays of n_tiles device pointers, each `elems_per_tile` elements of
+ *                    `dtype`, 16-byte aligned; elems_per_tile must be a multiple of 8
+ *   has_cache        device, n_tiles bytes (0/1)
+ *   scores           device, n_tiles floats (out);  recompute: device, n_tiles bytes (out)
+ *   workspace        device scratch of at least sg_workspace_bytes(n_tiles)
+ * Partial sums are fp32 per thread and fp64 across threads in a fixed order, so results are
+ * bit-reproducible from run to run.
+ */
+int sg_cache_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache,
+                  int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float threshold,
+                  float* scores, uint8_t* recompute, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
+/* Buffers of one tiled step.  All arrays of pointers are host arrays of device pointers. */
+typedef struct sg_step_io {
+  /* Canvas mode (gate off): q, k, v are canvas tensors and every tile is recomputed.        */
+  const void* q;
+  const void* k;
+  const void* v;
+  /* Cached mode: tile_x[i] is tile i's packed input [3][heads][T][tile_h][tile_w][d] (Q, K, V
+   * one after the other); q, k, v must then be NULL.                                        */
+  const void* const* tile_x;
+  void* const* cache_x;   /* cached mode: per-tile cached input, same shape as tile_x[i]; refreshed on recompute */
+  void* const* cache_out; /* both modes: per-tile packed attention output; the blend reads these                */
+  uint8_t* has_cache;     /* cached mode: device, n_tiles bytes, in/out (set to 1 on recompute)                 */
+  float threshold;        /* cached mode: cache threshold; < 0 switches the gate off (all tiles recompute)      */
+  float* scores;          /* cached mode: device, n_tiles floats (out)                                          */
+  uint8_t* recompute;     /* cached mode: device, n_tiles bytes (out)                                           */
+  void* grid_out;         /* device, canvas tensor (out)                                                        */
+  void* workspace;        /* cached mode: device scratch, sg_workspace_bytes(n_tiles)                           */
+  size_t workspace_bytes;
+} sg_step_io;
+
+/*
+ * One stage-2 step over all tiles (Algorithm 1 loop body; Section 5.1: Tile Dispatcher ->
+ * Threshold Comparator -> recompute or reuse -> Tile Fuser).
+ *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.
+ *   cached mode: gate every tile on tile_x[i] against cache_x[i]; for the tiles to recompute
+ *     cache_out[i] = attention(tile_x[i]), cache_x[i] = tile_x[i], has_cache[i] = 1; reused
+ *     tiles keep their cache entries untouched (drift stays measured from the last recomputed
+ *     step); grid_out = Fuse of all cache_out.
+ * The decisions stay on the device: skipped tiles cost one empty launch, nothing is read back.
+ */
+int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUPERGEN_TILE_H */

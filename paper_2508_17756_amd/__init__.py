@@ -1,0 +1,7 @@
+"""MI355X-native tile-denoising hot path: Python binding over libsupergen_tile.so."""
+from .binding import (  # noqa: F401
+    SG_F32, SG_BF16, SG_OK, SG_ERR_INVALID_ARG, SG_ERR_UNSUPPORTED, SG_ERR_WORKSPACE, SG_ERR_HIP,
+    SgError, sg_problem, sg_step_io, load_library, library_path, make_problem,
+    sg_version, sg_status_string, sg_problem_validate, sg_workspace_bytes,
+    sg_tile_attention, sg_tile_blend, sg_cache_gate, sg_denoise_step_tiled,
+)

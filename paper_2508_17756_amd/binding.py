@@ -1,0 +1,199 @@
+"""ctypes binding with the same names as the C ABI in include/supergen_tile.h.
+
+Argument marshalling only: tensors are torch tensors used as device buffers (their
+data_ptr() and the current HIP stream are handed to the library); every step of the path
+runs inside the library's kernels.  There is no fallback: if the shared library has not
+been built, loading raises.
+"""
+import ctypes
+import os
+
+SG_F32, SG_BF16 = 0, 1
+SG_OK, SG_ERR_INVALID_ARG, SG_ERR_UNSUPPORTED, SG_ERR_WORKSPACE, SG_ERR_HIP = 0, -1, -2, -3, -4
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class SgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        text = load_library().sg_status_string(status).decode()
+        super().__init__("%s failed: %s (%d)" % (where, text, status))
+
+
+class sg_problem(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("tile_h", ctypes.c_int32), ("tile_w", ctypes.c_int32),
+                ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32),
+                ("n_tile_rows", ctypes.c_int32), ("n_tile_cols", ctypes.c_int32),
+                ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("grid_stride_token", ctypes.c_int64), ("grid_stride_head", ctypes.c_int64)]
+
+
+class sg_step_io(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("tile_x", ctypes.POINTER(ctypes.c_void_p)),
+                ("cache_x", ctypes.POINTER(ctypes.c_void_p)),
+                ("cache_out", ctypes.POINTER(ctypes.c_void_p)),
+                ("has_cache", ctypes.c_void_p),
+                ("threshold", ctypes.c_float),
+                ("scores", ctypes.c_void_p), ("recompute", ctypes.c_void_p),
+                ("grid_out", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+def library_path():
+    return os.path.join(_PKG, "libsupergen_tile.so")
+
+
+def load_library():
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError("%s is missing: build it with `python -m paper_2508_17756_amd.build` "
+                          "(there is no CPU fallback)" % path)
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.sg_version.restype = ctypes.c_char_p
+    lib.sg_version.argtypes = []
+    lib.sg_status_string.restype = ctypes.c_char_p
+    lib.sg_status_string.argtypes = [ctypes.c_int]
+    lib.sg_last_hip_error.restype = ctypes.c_int
+    lib.sg_last_hip_error.argtypes = []
+    lib.sg_problem_validate.restype = ctypes.c_int
+    lib.sg_problem_validate.argtypes = [ctypes.POINTER(sg_problem)]
+    lib.sg_workspace_bytes.restype = ctypes.c_int
+    lib.sg_workspace_bytes.argtypes = [i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.sg_tile_attention.restype = ctypes.c_int
+    lib.sg_tile_attention.argtypes = [ctypes.POINTER(sg_problem), vp, vp, vp, i32, i32, vp, vp]
+    lib.sg_tile_blend.restype = ctypes.c_int
+    lib.sg_tile_blend.argtypes = [ctypes.POINTER(sg_problem), pp, vp, vp]
+    lib.sg_cache_gate.restype = ctypes.c_int
+    lib.sg_cache_gate.argtypes = [pp, pp, vp, i32, i64, i32, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sg_denoise_step_tiled.restype = ctypes.c_int
+    lib.sg_denoise_step_tiled.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_step_io), vp]
+    _LIB = lib
+    return lib
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return SG_F32
+    if t.dtype == torch.bfloat16:
+        return SG_BF16
+    raise TypeError("tensors must be float32 or bfloat16")
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _ptr_array(tensors):
+    arr = (ctypes.c_void_p * max(1, len(tensors)))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _check(status, where):
+    if status != SG_OK:
+        raise SgError(status, where)
+
+
+def make_problem(geom, dtype=None, token_major=False):
+    """sg_problem for a geometry object with the fields of synthetic.TileGeometry (or any
+    object with T, H, W, tile_h, tile_w, stride_h, stride_w, n_tile_rows, n_tile_cols, heads,
+    head_dim, scale, dtype); canvas tensors are [heads][T][H][W][d] unless token_major."""
+    p = sg_problem()
+    for f in ("T", "H", "W", "tile_h", "tile_w", "stride_h", "stride_w", "n_tile_rows", "n_tile_cols",
+              "heads", "head_dim"):
+        setattr(p, f, int(getattr(geom, f)))
+    d = dtype if dtype is not None else geom.dtype
+    p.dtype = {"f32": SG_F32, "bf16": SG_BF16, SG_F32: SG_F32, SG_BF16: SG_BF16}[d]
+    p.scale = float(geom.scale)
+    if token_major:
+        p.grid_stride_token = p.heads * p.head_dim
+        p.grid_stride_head = p.head_dim
+    else:
+        p.grid_stride_token = p.head_dim
+        p.grid_stride_head = p.T * p.H * p.W * p.head_dim
+    return p
+
+
+# ------------------------------------------------------------------ the ABI, same names
+def sg_version():
+    return load_library().sg_version().decode()
+
+
+def sg_status_string(status):
+    return load_library().sg_status_string(int(status)).decode()
+
+
+def sg_problem_validate(p):
+    return load_library().sg_problem_validate(ctypes.byref(p))
+
+
+def sg_workspace_bytes(n_tiles):
+    out = ctypes.c_size_t(0)
+    _check(load_library().sg_workspace_bytes(int(n_tiles), ctypes.byref(out)), "sg_workspace_bytes")
+    return out.value
+
+
+def sg_tile_attention(p, q, k, v, tile_row, tile_col, out_tile):
+    """Enqueues the attention of tile (tile_row, tile_col) on the current stream."""
+    st = load_library().sg_tile_attention(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), int(tile_row),
+                                          int(tile_col), _ptr(out_tile), _stream())
+    _check(st, "sg_tile_attention")
+    return out_tile
+
+
+def sg_tile_blend(p, tile_out, grid_out):
+    arr = _ptr_array(tile_out)
+    st = load_library().sg_tile_blend(ctypes.byref(p), arr, _ptr(grid_out), _stream())
+    _check(st, "sg_tile_blend")
+    return grid_out
+
+
+def sg_cache_gate(x_cur, x_cached, has_cache, threshold, scores, recompute, workspace, elems_per_tile=None):
+    n = len(x_cur)
+    elems = int(elems_per_tile if elems_per_tile is not None else (x_cur[0].numel() if n else 0))
+    dt = _dtype_code(x_cur[0]) if n else SG_BF16
+    st = load_library().sg_cache_gate(_ptr_array(x_cur), _ptr_array(x_cached), _ptr(has_cache), n, elems, dt,
+                                      float(threshold), _ptr(scores), _ptr(recompute), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                      _stream())
+    _check(st, "sg_cache_gate")
+    return scores, recompute
+
+
+def sg_denoise_step_tiled(p, grid_out, cache_out, q=None, k=None, v=None, tile_x=None, cache_x=None,
+                          has_cache=None, threshold=-1.0, scores=None, recompute=None, workspace=None):
+    io = sg_step_io()
+    io.q, io.k, io.v = _ptr(q), _ptr(k), _ptr(v)
+    keep = [_ptr_array(cache_out)]
+    io.cache_out = keep[0]
+    if tile_x is not None:
+        keep += [_ptr_array(tile_x), _ptr_array(cache_x)]
+        io.tile_x, io.cache_x = keep[1], keep[2]
+    io.has_cache = _ptr(has_cache)
+    io.threshold = float(threshold)
+    io.scores, io.recompute = _ptr(scores), _ptr(recompute)
+    io.grid_out = _ptr(grid_out)
+    io.workspace = _ptr(workspace)
+    io.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    st = load_library().sg_denoise_step_tiled(ctypes.byref(p), ctypes.byref(io), _stream())
+    _check(st, "sg_denoise_step_tiled")
+    return grid_out

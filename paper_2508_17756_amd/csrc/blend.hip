@@ -1,0 +1,109 @@
+// Fuse / overlap blend of tile outputs into the canvas (paper Algorithm 1 "Fuse", Section 4.3).
+//
+// Gather form of the weighted scatter-accumulate-and-normalise: every canvas element pulls the
+// contributions of the tiles that cover it, with the separable ramp weights recomputed
+// analytically, and divides by the weight sum.  No accumulator or weight buffers, no atomics:
+// each tile-output element is read once and each canvas element written once, which is the
+// algorithmic HBM traffic.  One thread owns one 16-byte vector of the canvas.
+#include "sg_common.h"
+
+namespace sg {
+namespace {
+
+constexpr int kThreads = 256;
+
+struct BlendArgs {
+  const void* tile[SG_MAX_TILES];
+  int32_t T, H, W, th, tw, sh, sw, n_rows, n_cols, heads, d;
+  int32_t vec_per_token_log2;  // log2(d / elements per 16-byte vector)
+  float inv_oh1, inv_ow1;      // 1/(o+1) per axis
+  int64_t stride_token, stride_head;
+  uint32_t plane_vecs;         // H*W*vec_per_token
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float ramp(int i, int L, float inv_o1) {
+  // min(1, (i+1)/(o+1), (L-i)/(o+1))
+  return fminf(1.0f, fminf((float)(i + 1) * inv_o1, (float)(L - i) * inv_o1));
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void* __restrict__ grid_out) {
+  constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
+  const uint32_t v = blockIdx.x * kThreads + threadIdx.x;  // vector inside one (head, frame) plane
+  if (v >= a.plane_vecs) return;
+  const int plane = blockIdx.y;  // head * T + t
+  const int head = plane / a.T, t = plane - head * a.T;
+  const uint32_t token = v >> a.vec_per_token_log2;
+  const int cv = v & ((1u << a.vec_per_token_log2) - 1);
+  const int y = token / (uint32_t)a.W, x = token - y * a.W;
+
+  // tiles covering row y: tr*sh <= y < tr*sh + th
+  int tr_hi = y / a.sh; if (tr_hi > a.n_rows - 1) tr_hi = a.n_rows - 1;
+  int tr_lo = (y - a.th + a.sh) / a.sh; if (y - a.th + a.sh < 0) tr_lo = 0;   // ceil((y-th+1)/sh)
+  int tc_hi = x / a.sw; if (tc_hi > a.n_cols - 1) tc_hi = a.n_cols - 1;
+  int tc_lo = (x - a.tw + a.sw) / a.sw; if (x - a.tw + a.sw < 0) tc_lo = 0;
+
+  float acc[kPerVec];
+#pragma unroll
+  for (int c = 0; c < kPerVec; ++c) acc[c] = 0.f;
+  float wsum = 0.f;
+  for (int tr = tr_lo; tr <= tr_hi; ++tr) {
+    const int i = y - tr * a.sh;
+    const float wh = ramp(i, a.th, a.inv_oh1);
+    for (int tc = tc_lo; tc <= tc_hi; ++tc) {
+      const int j = x - tc * a.sw;
+      const float w = wh * ramp(j, a.tw, a.inv_ow1);
+      const int64_t tok = ((int64_t)(plane * a.th + i)) * a.tw + j;       // packed tile token index incl. head
+      const u32x4* src = (const u32x4*)a.tile[tr * a.n_cols + tc] + ((tok << a.vec_per_token_log2) + cv);
+      const u32x4 val = __builtin_nontemporal_load(src);
+      wsum += w;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (DT == SG_BF16) {
+          acc[2 * c] += w * bf16_bits_to_f32(val[c] & 0xffffu);
+          acc[2 * c + 1] += w * __uint_as_float(val[c] & 0xffff0000u);
+        } else {
+          acc[c] += w * __uint_as_float(val[c]);
+        }
+      }
+    }
+  }
+  const float inv = 1.0f / wsum;
+  u32x4 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (DT == SG_BF16) o[c] = pack_bf16x2(acc[2 * c] * inv, acc[2 * c + 1] * inv);
+    else o[c] = __float_as_uint(acc[c] * inv);
+  }
+  const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
+  const int64_t off = (int64_t)head * a.stride_head + n * a.stride_token + (int64_t)cv * kPerVec;
+  u32x4* dst = (u32x4*)((char*)grid_out + off * (DT == SG_BF16 ? 2 : 4));
+  __builtin_nontemporal_store(o, dst);
+}
+
+}  // namespace
+
+int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, hipStream_t s) {
+  BlendArgs a;
+  const int n_tiles = p.n_tile_rows * p.n_tile_cols;
+  for (int i = 0; i < SG_MAX_TILES; ++i) a.tile[i] = i < n_tiles ? tile_out[i] : nullptr;
+  a.T = p.T; a.H = p.H; a.W = p.W; a.th = p.tile_h; a.tw = p.tile_w; a.sh = p.stride_h; a.sw = p.stride_w;
+  a.n_rows = p.n_tile_rows; a.n_cols = p.n_tile_cols; a.heads = p.heads; a.d = p.head_dim;
+  const int per_vec = (p.dtype == SG_BF16) ? 8 : 4;
+  const int vpt = p.head_dim / per_vec;
+  int lg = 0; while ((1 << lg) < vpt) ++lg;
+  a.vec_per_token_log2 = lg;
+  a.inv_oh1 = 1.0f / (float)(p.tile_h - p.stride_h + 1);
+  a.inv_ow1 = 1.0f / (float)(p.tile_w - p.stride_w + 1);
+  a.stride_token = p.grid_stride_token; a.stride_head = p.grid_stride_head;
+  a.plane_vecs = (uint32_t)((int64_t)p.H * p.W * vpt);
+  dim3 grid((a.plane_vecs + kThreads - 1) / kThreads, p.heads * p.T);
+  if (p.dtype == SG_BF16) blend_kernel<SG_BF16><<<grid, kThreads, 0, s>>>(a, grid_out);
+  else blend_kernel<SG_F32><<<grid, kThreads, 0, s>>>(a, grid_out);
+  SG_HIP_TRY(hipGetLastError());
+  return SG_OK;
+}
+
+}  // namespace sg

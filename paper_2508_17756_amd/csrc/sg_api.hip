@@ -1,0 +1,183 @@
+// C ABI of libsupergen_tile: host-side argument checks and the order of launches.
+// Every step of the path runs in the HIP kernels of the sibling files; nothing is computed here.
+#include <cmath>
+#include "sg_common.h"
+
+namespace sg {
+
+static thread_local int g_last_hip_error = 0;
+
+int note_hip_error(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return SG_ERR_HIP;
+}
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+static int validate(const sg_problem* p) {
+  if (!p) return SG_ERR_INVALID_ARG;
+  if (p->T <= 0 || p->H <= 0 || p->W <= 0 || p->tile_h <= 0 || p->tile_w <= 0 || p->stride_h <= 0 ||
+      p->stride_w <= 0 || p->n_tile_rows <= 0 || p->n_tile_cols <= 0 || p->heads <= 0 || p->head_dim <= 0)
+    return SG_ERR_INVALID_ARG;
+  if (p->dtype != SG_F32 && p->dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (!std::isfinite(p->scale) || p->scale <= 0.f) return SG_ERR_INVALID_ARG;
+  if (p->stride_h > p->tile_h || p->stride_w > p->tile_w) return SG_ERR_INVALID_ARG;  // gaps between tiles
+  if ((int64_t)(p->n_tile_rows - 1) * p->stride_h + p->tile_h != p->H) return SG_ERR_INVALID_ARG;
+  if ((int64_t)(p->n_tile_cols - 1) * p->stride_w + p->tile_w != p->W) return SG_ERR_INVALID_ARG;
+  if (p->grid_stride_token < p->head_dim || p->grid_stride_head <= 0) return SG_ERR_INVALID_ARG;
+  if ((p->grid_stride_token & 7) || (p->grid_stride_head & 7)) return SG_ERR_INVALID_ARG;
+  if (p->head_dim != 64 && p->head_dim != 128) return SG_ERR_UNSUPPORTED;
+  if (p->dtype == SG_BF16 && p->head_dim != 128) return SG_ERR_UNSUPPORTED;
+  if ((int64_t)p->n_tile_rows * p->n_tile_cols > SG_MAX_TILES) return SG_ERR_UNSUPPORTED;
+  if ((int64_t)p->T * p->tile_h * p->tile_w >= (1ll << 31)) return SG_ERR_UNSUPPORTED;
+  if ((int64_t)p->heads * p->T >= 65536) return SG_ERR_UNSUPPORTED;
+  // kernels address canvas tensors with 32-bit offsets in units of 8 elements
+  const int64_t span = (int64_t)(p->heads - 1) * p->grid_stride_head +
+                       ((int64_t)p->T * p->H * p->W - 1) * p->grid_stride_token + p->head_dim;
+  if (span >= (1ll << 35)) return SG_ERR_UNSUPPORTED;
+  if ((int64_t)p->H * p->W * (p->head_dim / 4) >= (1ll << 32)) return SG_ERR_UNSUPPORTED;
+  return SG_OK;
+}
+
+static TileView make_view(const sg_problem& p, int tile_row, int tile_col) {
+  TileView tv;
+  tv.stride_token = p.grid_stride_token;
+  tv.stride_head = p.grid_stride_head;
+  tv.T = p.T; tv.H = p.H; tv.W = p.W; tv.th = p.tile_h; tv.tw = p.tile_w;
+  tv.N = p.T * p.tile_h * p.tile_w;
+  tv.base = ((int64_t)tile_row * p.stride_h * p.W + (int64_t)tile_col * p.stride_w) * p.grid_stride_token;
+  return tv;
+}
+
+static int attention_dispatch(const sg_problem& p, const TileView& tv, const void* q, const void* k, const void* v,
+                              void* out, const uint8_t* run_flag, hipStream_t s) {
+  if (p.dtype == SG_F32)
+    return launch_attention_f32(tv, p.heads, p.head_dim, p.scale, (const float*)q, (const float*)k, (const float*)v,
+                                (float*)out, run_flag, s);
+  return launch_attention_bf16(tv, p.heads, p.head_dim, p.scale, q, k, v, out, run_flag, s);
+}
+
+}  // namespace sg
+
+using namespace sg;
+
+extern "C" {
+
+const char* sg_version(void) { return "0.1"; }
+
+const char* sg_status_string(int status) {
+  switch (status) {
+    case SG_OK: return "ok";
+    case SG_ERR_INVALID_ARG: return "invalid argument";
+    case SG_ERR_UNSUPPORTED: return "unsupported problem";
+    case SG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SG_ERR_HIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int sg_last_hip_error(void) { return g_last_hip_error; }
+
+int sg_problem_validate(const sg_problem* p) { return validate(p); }
+
+int sg_workspace_bytes(int32_t n_tiles, size_t* out_bytes) {
+  if (!out_bytes || n_tiles < 0) return SG_ERR_INVALID_ARG;
+  *out_bytes = gate_workspace_bytes(n_tiles);
+  return SG_OK;
+}
+
+int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const void* v, int32_t tile_row,
+                      int32_t tile_col, void* out_tile, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!q || !k || !v || !out_tile) return SG_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out_tile)) return SG_ERR_INVALID_ARG;
+  if (tile_row < 0 || tile_row >= p->n_tile_rows || tile_col < 0 || tile_col >= p->n_tile_cols)
+    return SG_ERR_INVALID_ARG;
+  return attention_dispatch(*p, make_view(*p, tile_row, tile_col), q, k, v, out_tile, nullptr, (hipStream_t)stream);
+}
+
+int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_out, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!tile_out || !grid_out || !aligned16(grid_out)) return SG_ERR_INVALID_ARG;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
+  for (int i = 0; i < n_tiles; ++i)
+    if (!tile_out[i] || !aligned16(tile_out[i])) return SG_ERR_INVALID_ARG;
+  return launch_blend(*p, tile_out, grid_out, (hipStream_t)stream);
+}
+
+int sg_cache_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache, int32_t n_tiles,
+                  int64_t elems_per_tile, int32_t dtype, float threshold, float* scores, uint8_t* recompute,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_tiles < 0 || elems_per_tile < 0) return SG_ERR_INVALID_ARG;
+  if (dtype != SG_F32 && dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (std::isnan(threshold)) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (!x_cur || !x_cached || !has_cache || !scores || !recompute) return SG_ERR_INVALID_ARG;
+  for (int i = 0; i < n_tiles; ++i) {
+    if (!x_cur[i] || !aligned16(x_cur[i])) return SG_ERR_INVALID_ARG;
+    if (!x_cached[i] || !aligned16(x_cached[i])) return SG_ERR_INVALID_ARG;
+  }
+  if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  return launch_gate(x_cur, x_cached, has_cache, n_tiles, elems_per_tile, dtype, threshold, scores, recompute,
+                     workspace, (hipStream_t)stream);
+}
+
+int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!io || !io->cache_out || !io->grid_out || !aligned16(io->grid_out)) return SG_ERR_INVALID_ARG;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
+  for (int i = 0; i < n_tiles; ++i)
+    if (!io->cache_out[i] || !aligned16(io->cache_out[i])) return SG_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t esz = p->dtype == SG_BF16 ? 2 : 4;
+  const int64_t tile_elems = (int64_t)p->heads * p->T * p->tile_h * p->tile_w * p->head_dim;
+
+  if (!io->tile_x) {  // canvas mode: every tile is recomputed from the shared canvas tensors
+    if (!io->q || !io->k || !io->v) return SG_ERR_INVALID_ARG;
+    if (!aligned16(io->q) || !aligned16(io->k) || !aligned16(io->v)) return SG_ERR_INVALID_ARG;
+    for (int tr = 0; tr < p->n_tile_rows; ++tr)
+      for (int tc = 0; tc < p->n_tile_cols; ++tc) {
+        st = attention_dispatch(*p, make_view(*p, tr, tc), io->q, io->k, io->v,
+                                io->cache_out[tr * p->n_tile_cols + tc], nullptr, s);
+        if (st != SG_OK) return st;
+      }
+    return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, s);
+  }
+
+  // cached mode
+  if (io->q || io->k || io->v) return SG_ERR_INVALID_ARG;
+  if (!io->cache_x || !io->has_cache || !io->scores || !io->recompute) return SG_ERR_INVALID_ARG;
+  if (std::isnan(io->threshold)) return SG_ERR_INVALID_ARG;
+  for (int i = 0; i < n_tiles; ++i) {
+    if (!io->tile_x[i] || !aligned16(io->tile_x[i])) return SG_ERR_INVALID_ARG;
+    if (!io->cache_x[i] || !aligned16(io->cache_x[i])) return SG_ERR_INVALID_ARG;
+  }
+  if (!io->workspace || (((uintptr_t)io->workspace) & 255u) || io->workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  // threshold < 0: every score (>= 0 or +inf) is at or above it, so every tile recomputes
+  st = launch_gate(io->tile_x, (const void* const*)io->cache_x, io->has_cache, n_tiles, 3 * tile_elems, p->dtype,
+                   io->threshold, io->scores, io->recompute, io->workspace, s);
+  if (st != SG_OK) return st;
+  // a packed tile is a canvas that is exactly one tile
+  sg_problem tp = *p;
+  tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+  tp.grid_stride_token = p->head_dim;
+  tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
+  const TileView tv = make_view(tp, 0, 0);
+  for (int i = 0; i < n_tiles; ++i) {
+    const char* x = (const char*)io->tile_x[i];
+    st = attention_dispatch(tp, tv, x, x + tile_elems * esz, x + 2 * tile_elems * esz, io->cache_out[i],
+                            io->recompute + i, s);
+    if (st != SG_OK) return st;
+  }
+  st = launch_cache_refresh(io->tile_x, io->cache_x, io->recompute, io->has_cache, n_tiles,
+                            3 * tile_elems * (int64_t)esz, s);
+  if (st != SG_OK) return st;
+  return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, s);
+}
+
+}  // extern "C"

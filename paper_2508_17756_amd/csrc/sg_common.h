@@ -1,0 +1,59 @@
+// Internal declarations shared by the HIP translation units of libsupergen_tile.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "supergen_tile.h"
+
+namespace sg {
+
+// Records a failed HIP call for sg_last_hip_error() and maps it to SG_ERR_HIP.
+int note_hip_error(hipError_t e);
+#define SG_HIP_TRY(expr)                                  \
+  do {                                                    \
+    hipError_t sg_e_ = (expr);                            \
+    if (sg_e_ != hipSuccess) return sg::note_hip_error(sg_e_); \
+  } while (0)
+
+// Canvas addressing of one tile, in elements, resolved on the host.
+struct TileView {
+  int64_t base;          // element offset of tile token (0,0,0), head 0
+  int64_t stride_token;  // elements between canvas tokens
+  int64_t stride_head;
+  int32_t T, H, W;       // canvas
+  int32_t th, tw;        // tile
+  int32_t N;             // T*th*tw tokens
+};
+
+// Launchers (each validates nothing: the API layer has already done so).
+int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const float* q,
+                         const float* k, const float* v, float* out, const uint8_t* run_flag,
+                         hipStream_t s);
+int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q,
+                          const void* k, const void* v, void* out, const uint8_t* run_flag,
+                          hipStream_t s);
+int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, hipStream_t s);
+int launch_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache,
+                int n_tiles, int64_t elems, int dtype, float threshold, float* scores,
+                uint8_t* recompute, void* ws, hipStream_t s);
+int launch_cache_refresh(const void* const* src, void* const* dst, const uint8_t* recompute,
+                         uint8_t* has_cache, int n_tiles, int64_t bytes_per_tile, hipStream_t s);
+
+// Gate scratch: per tile kGateBlocks (num, den) fp64 pairs.
+constexpr int kGateBlocks = 128;
+inline size_t gate_workspace_bytes(int n_tiles) {
+  return (size_t)(n_tiles > 0 ? n_tiles : 1) * kGateBlocks * 2 * sizeof(double);
+}
+
+// bf16 <-> fp32 on the device.
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {  // round to nearest even
+  __bf16 b = (__bf16)f;
+  return (uint32_t)__builtin_bit_cast(unsigned short, b);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+}  // namespace sg

@@ -1,0 +1,64 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, validates problems and rejects bad arguments before any launch."""
+import ctypes
+import re
+
+import pytest
+
+import paper_2508_17756_amd as sg
+from synthetic import CONFIGS
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    header = open(f"{repo_root}/include/supergen_tile.h").read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(sg_[a-z_]+)\s*\(", header))
+    assert {"sg_tile_attention", "sg_tile_blend", "sg_cache_gate", "sg_denoise_step_tiled"} <= names
+    lib = sg.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sg.sg_version() == "0.1"
+    assert sg.sg_status_string(sg.SG_ERR_WORKSPACE).startswith("workspace")
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(sg.sg_problem) == 13 * 4 + 4 + 16      # 13 int32/float + padding + 2 int64
+    assert sg.sg_problem.grid_stride_token.offset == 56
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_benchmark_configs_validate(name):
+    assert sg.sg_problem_validate(sg.make_problem(CONFIGS[name])) == sg.SG_OK
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("T", 0, sg.SG_ERR_INVALID_ARG), ("tile_h", 11, sg.SG_ERR_INVALID_ARG),       # tiles no longer cover H
+    ("stride_w", 11, sg.SG_ERR_INVALID_ARG),                                       # gap between tiles
+    ("dtype", 5, sg.SG_ERR_INVALID_ARG), ("scale", float("nan"), sg.SG_ERR_INVALID_ARG),
+    ("scale", 0.0, sg.SG_ERR_INVALID_ARG), ("grid_stride_token", 60, sg.SG_ERR_INVALID_ARG),
+    ("head_dim", 96, sg.SG_ERR_UNSUPPORTED),
+])
+def test_invalid_problems(field, value, status):
+    p = sg.make_problem(CONFIGS["tiny_f32"])
+    setattr(p, field, value)
+    if field == "head_dim":
+        p.grid_stride_token = 96
+    assert sg.sg_problem_validate(p) == status
+
+
+def test_null_and_workspace_checks_need_no_gpu():
+    lib = sg.load_library()
+    p = sg.make_problem(CONFIGS["tiny_f32"])
+    assert sg.sg_problem_validate(p) == 0
+    assert lib.sg_problem_validate(None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_attention(ctypes.byref(p), None, None, None, 0, 0, None, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_attention(ctypes.byref(p), 16, 16, 16, 0, 5, 16, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_attention(ctypes.byref(p), 16, 16, 8, 0, 0, 16, None) == sg.SG_ERR_INVALID_ARG   # misaligned
+    assert lib.sg_tile_blend(ctypes.byref(p), None, None, None) == sg.SG_ERR_INVALID_ARG
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    assert lib.sg_cache_gate(arr, arr, 256, 2, 64, sg.SG_BF16, 0.05, 256, 256, None, 0, None) == sg.SG_ERR_WORKSPACE
+    assert lib.sg_cache_gate(arr, arr, 256, 2, 64, sg.SG_BF16, 0.05, 256, 256, 256, 16, None) == sg.SG_ERR_WORKSPACE
+    assert lib.sg_cache_gate(arr, arr, 256, -1, 64, sg.SG_BF16, 0.05, 256, 256, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_cache_gate(arr, arr, 256, 2, 64, 9, 0.05, 256, 256, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_denoise_step_tiled(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG
+    assert sg.sg_workspace_bytes(20) >= 20 * 2 * 8

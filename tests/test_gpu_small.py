@@ -1,0 +1,233 @@
+"""GPU parity at sizes the fp64 oracle finishes in seconds: every entry point of the C ABI
+against the oracle, element by element, on seeded inputs spanning several blocks and ragged
+tails."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_17756_amd as sg
+from synthetic import CONFIGS, TileGeometry, randn_tensor, torch_dtype, scaled_down, eps_table, perturb_
+from gpu_util import (to_f64, errors, assert_close, canvas_qkv, gpu_tile_attention,
+                      oracle_tile_attention_full)
+
+pytestmark = pytest.mark.gpu
+
+
+def _geom(name, T, H, W, th, tw, sh, sw, heads, d, dtype, seed):
+    nr = (H - th) // sh + 1 if th < H else 1
+    nc = (W - tw) // sw + 1 if tw < W else 1
+    return TileGeometry(name, T, H, W, th, tw, sh, sw, nr, nc, heads, d, dtype, seed)
+
+
+# ------------------------------------------------------------------ attention
+def test_attention_tiny_f32_all_tiles():
+    g = CONFIGS["tiny_f32"]
+    q, k, v = canvas_qkv(g)
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            got = gpu_tile_attention(g, q, k, v, tr, tc)
+            assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, tr, tc), "f32", f"tile {tr},{tc}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_attention_f32_ragged(d):
+    g = _geom("f32r", 2, 9, 11, 9, 11, 9, 11, 3, d, "f32", 11)      # N = 198: 4 workgroups, ragged
+    q, k, v = canvas_qkv(g)
+    assert_close(to_f64(gpu_tile_attention(g, q, k, v, 0, 0)), oracle_tile_attention_full(g, q, k, v, 0, 0), "f32")
+
+
+BF16_CASES = [
+    # name, T, H, W, th, tw, sh, sw, heads: packed tiles (linear addressing) and canvas views
+    ("packed_n576", 3, 12, 16, 12, 16, 12, 16, 2),      # 576 = 2*256 + 64, 9 full key blocks
+    ("packed_n429", 3, 11, 13, 11, 13, 11, 13, 2),      # ragged: 429 = 256 + 173 ; 6*64 + 45
+    ("packed_n273", 3, 7, 13, 7, 13, 7, 13, 3),         # key tail 17 < 32: second half block all masked
+    ("packed_n40", 1, 5, 8, 5, 8, 5, 8, 1),             # fewer keys than one block
+    ("view_2x2", 3, 16, 22, 10, 14, 6, 8, 2),           # overlapping tiles read in place, N = 420
+    ("view_3x3", 2, 20, 40, 12, 24, 4, 8, 2),           # N = 576, triple row coverage
+]
+
+
+@pytest.mark.parametrize("case", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_attention_bf16_small(case):
+    name, T, H, W, th, tw, sh, sw, heads = case
+    g = _geom(name, T, H, W, th, tw, sh, sw, heads, 128, "bf16", 21)
+    q, k, v = canvas_qkv(g)
+    for tr, tc in {(0, 0), (g.n_tile_rows - 1, g.n_tile_cols - 1), (g.n_tile_rows - 1, 0)}:
+        got = gpu_tile_attention(g, q, k, v, tr, tc)
+        ma, rl = assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, tr, tc), "bf16", f"{name} {tr},{tc}")
+        print(f"{name} tile({tr},{tc}) max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_attention_bf16_token_major_layout():
+    """[T][H][W][heads][d] canvas through the stride fields."""
+    g = _geom("tokmaj", 2, 12, 18, 8, 10, 4, 8, 3, 128, "bf16", 31)
+    qkv_hm = canvas_qkv(g)
+    qkv_tm = [t.permute(1, 2, 3, 0, 4).contiguous() for t in qkv_hm]
+    out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
+    sg.sg_tile_attention(sg.make_problem(g, token_major=True), *qkv_tm, 1, 1, out)
+    assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv_hm, 1, 1), "bf16")
+
+
+def test_attention_bf16_large_logits_and_constant_v():
+    """Scores far from N(0,1): softmax concentrates; constant V must come back exactly-ish."""
+    g = _geom("sharp", 2, 10, 16, 10, 16, 10, 16, 2, 128, "bf16", 41)
+    q, k, v = canvas_qkv(g)
+    q = (q.float() * 4).to(torch.bfloat16)
+    got = gpu_tile_attention(g, q, k, v, 0, 0)
+    assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, 0, 0), "bf16")
+    vc = torch.full_like(v, 0.75)
+    got = gpu_tile_attention(g, q, k, vc, 0, 0)
+    assert float((got.float() - 0.75).abs().max()) <= 0.75 * 2 ** -7
+
+
+# ------------------------------------------------------------------ blend
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ["tiny2x2", "triple3x2", "placement"])
+def test_blend_small(dtype, shape):
+    d = 64 if dtype == "f32" else 128
+    g = {"tiny2x2": replace(CONFIGS["tiny_f32"], dtype=dtype, head_dim=d),
+         "triple3x2": _geom("tr", 2, 9, 7, 5, 4, 2, 3, 3, d, dtype, 51),
+         "placement": _geom("pl", 2, 8, 6, 4, 3, 4, 3, 2, d, dtype, 52)}[shape]
+    tiles = [randn_tensor(g.tile_shape, dtype, 600 + i).cuda() for i in range(g.n_tiles)]
+    out = torch.full(g.grid_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    sg.sg_tile_blend(sg.make_problem(g), tiles, out)
+    ref = oracle.blend([to_f64(t) for t in tiles], g)
+    assert_close(to_f64(out), ref, dtype, shape)
+    if shape == "placement":      # o = 0: pure placement, bit exact
+        assert np.array_equal(to_f64(out)[:, :, 0:4, 0:3, :], to_f64(tiles[0]))
+
+
+def test_blend_token_major_canvas():
+    g = _geom("tm", 2, 9, 7, 5, 4, 2, 3, 3, 128, "bf16", 53)
+    tiles = [randn_tensor(g.tile_shape, "bf16", 700 + i).cuda() for i in range(g.n_tiles)]
+    out = torch.empty((g.T, g.H, g.W, g.heads, g.head_dim), dtype=torch.bfloat16, device="cuda")
+    sg.sg_tile_blend(sg.make_problem(g, token_major=True), tiles, out)
+    ref = oracle.blend([to_f64(t) for t in tiles], g)
+    assert_close(to_f64(out.permute(3, 0, 1, 2, 4)), ref, "bf16")
+
+
+# ------------------------------------------------------------------ gate
+def _gate(x_cur, x_cached, has_cache, thr):
+    n = len(x_cur)
+    hc = torch.tensor(has_cache, dtype=torch.uint8, device="cuda")
+    scores = torch.full((max(n, 1),), -1.0, dtype=torch.float32, device="cuda")
+    rec = torch.full((max(n, 1),), 7, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    sg.sg_cache_gate(x_cur, x_cached, hc, thr, scores, rec, ws)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy()[:n], rec.cpu().numpy()[:n].astype(bool)
+
+
+def _check_gate(x_cur, x_cached, has_cache, thr):
+    s, r = _gate(x_cur, x_cached, has_cache, thr)
+    so, ro = oracle.cache_gate([to_f64(t) for t in x_cur], [to_f64(t) for t in x_cached], has_cache,
+                               float(np.float32(thr)))
+    for i in range(len(x_cur)):
+        if np.isinf(so[i]):
+            assert np.isinf(s[i]) and r[i]
+            continue
+        assert abs(s[i] - so[i]) <= 2e-6 * max(1.0, so[i]), (i, s[i], so[i])
+        if abs(so[i] - float(np.float32(thr))) > 1e-4:       # decisions bit exact outside the band
+            assert r[i] == ro[i], (i, s[i], so[i])
+    return s, r
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("elems", [8, 1000, 4099, 3 * 2 * 3 * 10 * 10 * 64, 1 << 20])
+def test_gate_small(dtype, elems):
+    n = 5
+    cached = [randn_tensor((elems,), dtype, 800 + i).cuda() for i in range(n)]
+    eps = [0.0, 0.01, 0.1, 0.06, 0.04]
+    cur = [perturb_(c.clone(), e, 900 + i) for i, (c, e) in enumerate(zip(cached, eps))]
+    s, r = _check_gate(cur, cached, [1, 1, 1, 1, 0], 0.05)
+    assert s[0] == 0.0 and not r[0] and r[4]
+
+
+def test_gate_edge_cases():
+    x = randn_tensor((4096,), "bf16", 1).cuda()
+    z = torch.zeros_like(x)
+    s, r = _check_gate([x, x, z], [z, x, z], [1, 1, 1], 0.05)
+    assert np.isinf(s[0]) and r[0] and not r[1] and r[2]        # zero cache -> +inf -> recompute
+    # exact tie: x_cur = (1 + 1/16) x_cached on exactly representable data, threshold 1/16
+    xc = (torch.arange(4096, device="cuda") % 7 + 1).float()
+    s, r = _gate([xc * 1.0625, xc * 1.03125], [xc, xc], [1, 1], 0.0625)
+    assert s[0] == 0.0625 and r[0] and s[1] == 0.03125 and not r[1]
+    # negative threshold: everything recomputes; zero tiles: no-op
+    s, r = _gate([x], [x], [1], -1.0)
+    assert r[0]
+    _gate([], [], [], 0.05)
+
+
+def test_gate_many_tiles():
+    n = 70                                            # more than one launch's worth of pointers
+    cached = [randn_tensor((2048,), "bf16", 1000 + i).cuda() for i in range(n)]
+    cur = [perturb_(c.clone(), 0.1 if i % 3 == 0 else 0.01, 2000 + i) for i, c in enumerate(cached)]
+    s, r = _check_gate(cur, cached, [1] * n, 0.05)
+    assert list(r) == [i % 3 == 0 for i in range(n)]
+
+
+# ------------------------------------------------------------------ tiled step
+def test_step_canvas_mode_tiny_f32():
+    g = CONFIGS["tiny_f32"]
+    q, k, v = canvas_qkv(g)
+    cache_out = [torch.empty(g.tile_shape, dtype=torch.float32, device="cuda") for _ in range(g.n_tiles)]
+    canvas = torch.empty(g.grid_shape, dtype=torch.float32, device="cuda")
+    sg.sg_denoise_step_tiled(sg.make_problem(g), canvas, cache_out, q=q, k=k, v=v)
+    outs = [oracle_tile_attention_full(g, q, k, v, tr, tc) for tr in range(2) for tc in range(2)]
+    assert_close(to_f64(canvas), oracle.blend(outs, g), "f32")
+
+
+def test_step_cached_mode_bf16_three_steps():
+    g = _geom("stepc", 2, 14, 20, 8, 12, 6, 8, 2, 128, "bf16", 61)       # 2x2 tiles, N = 192
+    n = g.n_tiles
+    canvas_in = canvas_qkv(g)
+    tile_x = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            r0, c0 = tr * g.stride_h, tc * g.stride_w
+            tile_x.append(torch.stack([t[:, :, r0:r0 + g.tile_h, c0:c0 + g.tile_w, :] for t in canvas_in]).contiguous())
+    cache_x = [torch.zeros_like(t) for t in tile_x]
+    cache_out = [torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    has_cache = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    rec = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    p = sg.make_problem(g)
+    state = oracle.StepState(n)
+    eps = [[0, 0, 0, 0], [0.01, 0.1, 0.01, 0.1], [0.01, 0.01, 0.1, 0.01]]
+    expect = [[True] * 4, [False, True, False, True], [False, False, True, False]]
+    for step in range(3):
+        if step:
+            for i in range(n):
+                perturb_(tile_x[i], eps[step][i], 3000 + 10 * step + i)
+        sg.sg_denoise_step_tiled(p, canvas, cache_out, tile_x=tile_x, cache_x=cache_x, has_cache=has_cache,
+                                 threshold=0.05, scores=scores, recompute=rec, workspace=ws)
+        torch.cuda.synchronize()
+        ref_canvas, ref_s, ref_r = oracle.denoise_step_tiled(
+            [tuple(to_f64(t[j]) for j in range(3)) for t in tile_x], g, g.scale, state, float(np.float32(0.05)))
+        assert list(rec.cpu().numpy().astype(bool)) == list(ref_r) == expect[step]
+        got_s = scores.cpu().numpy()
+        for i in range(n):
+            assert (np.isinf(ref_s[i]) and np.isinf(got_s[i])) or abs(got_s[i] - ref_s[i]) < 2e-6
+        assert has_cache.cpu().numpy().all()
+        assert_close(to_f64(canvas), ref_canvas, "bf16", f"step {step}")
+        for i in range(n):                       # cache holds exactly the last recomputed input
+            assert np.array_equal(to_f64(cache_x[i]).ravel(), state.cache_x[i])
+
+
+# ------------------------------------------------------------------ error paths reach no kernel
+def test_bad_arguments_are_rejected():
+    g = CONFIGS["tiny_f32"]
+    q, k, v = canvas_qkv(g)
+    out = torch.empty(g.tile_shape, dtype=torch.float32, device="cuda")
+    with pytest.raises(sg.SgError) as e:
+        sg.sg_tile_attention(sg.make_problem(g), q, k, v, 2, 0, out)
+    assert e.value.status == sg.SG_ERR_INVALID_ARG
+    with pytest.raises(sg.SgError) as e:
+        sg.sg_tile_attention(sg.make_problem(g), q, k, None, 0, 0, out)
+    assert e.value.status == sg.SG_ERR_INVALID_ARG
