@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the tile-denoising hot path on one MI355X.
+
+A step is one call of sg_denoise_step_tiled in cached mode (cache gate -> tile attention on
+the tiles to recompute -> cache refresh -> Fuse) on synthetic inputs already resident in HBM.
+The default workload is the single 720p-sized tile (75,600 tokens, 40 heads x 128, bf16), the
+configuration the tile-attention TFLOP/s metric is quoted on; every timed step alternates
+between two inputs 0.1-noise apart, so the gate always orders a recompute and no work is
+skipped.  `value` = attention FLOPs (4 N^2 d heads, true N) / step time.
+
+Prints ONE JSON line.  Extra objects: `roofline` (the attention kernel alone, timed with HIP
+events on its stream), `kernels` (blend and gate GB/s at the 4K sizes, 4K step ms when
+--full), `cpu_baseline` (the fp64 oracle on a bounded row sample, host cores).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def time_calls(torch, fn, reps, warmup=1):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps      # ms per call
+
+
+def build_tile_inputs(torch, g, n_tiles, seed):
+    """Per-tile packed [3][heads][T][th][tw][d] inputs, N(0,1) bf16, generated on the device."""
+    from synthetic import randn_tensor
+    return [randn_tensor((3,) + g.tile_shape, g.dtype, seed + i, device="cuda") for i in range(n_tiles)]
+
+
+def cpu_baseline(torch, g, x, rows_per_head, heads):
+    """The fp64 oracle, as it stands, on a sample of query rows of the same tile."""
+    import oracle
+    from synthetic import sample_rows
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    N, d = g.tile_tokens, g.head_dim
+    rows = sample_rows(g.seed, N, rows_per_head)
+    host = [x[j][heads].to("cpu").to(torch.float64).numpy().reshape(len(heads), N, d) for j in range(3)]
+    t0 = time.perf_counter()
+    outs = [oracle.attention_rows(host[0][a][rows], host[1][a], host[2][a], g.scale) for a in range(len(heads))]
+    dt = time.perf_counter() - t0
+    flops = 4.0 * len(rows) * len(heads) * N * d
+    return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d query rows x %d heads of the %d-token tile, fp64 numpy, %.1f s" % (len(rows), len(heads), N, dt),
+            }, rows, outs
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="tile720p_bf16")
+    ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
+    ap.add_argument("--full", action="store_true", help="also time the 4K canvas step (20 tile attentions + blend)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+              "(tiles would shard across GPUs as described in DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2508_17756_amd as sg
+    from dataclasses import replace
+    from synthetic import CONFIGS, perturb_
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sg.load_library()
+    torch.cuda.set_device(0)
+    g = CONFIGS[args.workload]
+    if args.heads:
+        g = replace(g, heads=args.heads)
+    gt = g.single_tile() if g.n_tiles == 1 else g
+    n = gt.n_tiles
+    p = sg.make_problem(gt)
+
+    # ---- resident state: two inputs per tile 0.1-noise apart, cache, outputs
+    x_a = build_tile_inputs(torch, gt, n, g.seed)
+    x_b = [perturb_(t.clone(), 0.1, g.seed + 100 + i) for i, t in enumerate(x_a)]
+    cache_x = [torch.zeros_like(t) for t in x_a]
+    cache_out = [torch.zeros(gt.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    has_cache = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    scores = torch.zeros(n, dtype=torch.float32, device="cuda")
+    rec = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(gt.grid_shape, dtype=torch.bfloat16, device="cuda")
+    rec_log = []
+
+    def step(i):
+        sg.sg_denoise_step_tiled(p, canvas, cache_out, tile_x=(x_a if i % 2 == 0 else x_b), cache_x=cache_x,
+                                 has_cache=has_cache, threshold=0.05, scores=scores, recompute=rec, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = _events(torch)
+    t_wall = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        rec_log.append(rec.clone())          # device-side copy, read after the timed region
+    e1.record()
+    e1.synchronize()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / args.steps
+    wall_ms = (time.perf_counter() - t_wall) * 1e3 / args.steps
+    recomputed = int(sum(int(r.sum()) for r in rec_log))
+    if recomputed != n * args.steps:
+        print("bench.py: gate skipped work (%d of %d recomputes)" % (recomputed, n * args.steps), file=sys.stderr)
+        sys.exit(1)
+    flops_step = gt.attention_flops_per_tile * n
+    value = flops_step / (ms_step * 1e-3) * 1e-12
+
+    # ---- roofline of the dominant kernel: attention alone, same launch configuration
+    tile_problem = sg.make_problem(gt.single_tile())
+    E = int(np.prod(gt.tile_shape))
+
+    def att():
+        x = x_a[0]
+        sg.sg_tile_attention(tile_problem, x[0], x[1], x[2], 0, 0, cache_out[0])
+
+    ms_att = time_calls(torch, att, max(2, args.steps))
+    att_tflops = gt.attention_flops_per_tile / (ms_att * 1e-3) * 1e-12
+    out = {
+        "metric": "tile-attention TFLOP/s (% bf16 MFMA peak) + 4K tiled denoise-step ms",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": g.name, "tiles": n, "tile_tokens": gt.tile_tokens, "heads": gt.heads,
+                   "head_dim": gt.head_dim, "step": "gate+attention+cache refresh+blend (sg_denoise_step_tiled)"},
+        "pct_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "host_ms_per_step": round(wall_ms, 3),
+        "roofline": {"bound": "mfma", "achieved": round(att_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "attention_bf16_kernel", "ms_per_launch": round(ms_att, 3),
+                     "flops_per_launch": gt.attention_flops_per_tile},
+    }
+    if args.heads:
+        out["config"]["note"] = "head count overridden: not the benchmark configuration"
+
+    if not args.no_extras:
+        kernels = {}
+        # cache gate alone at this workload's sizes: reads x_cur and x_cached once
+        has_all = torch.ones(n, dtype=torch.uint8, device="cuda")
+        ms_gate = time_calls(torch, lambda: sg.sg_cache_gate(x_b, x_a, has_all, 0.05, scores, rec, ws), 10)
+        gate_bytes = 2.0 * 3 * E * 2 * n
+        kernels["gate"] = {"ms": round(ms_gate, 4), "GB/s": round(gate_bytes / ms_gate * 1e-6, 1),
+                           "frac_hbm_peak": round(gate_bytes / ms_gate * 1e-6 / PEAK_HBM_GBS, 4), "tiles": n}
+        del x_b, cache_x
+        # blend and gate at the 4K sizes (20 tiles of 75,600 tokens into a 21x135x240 canvas)
+        g4 = CONFIGS["canvas4k_bf16"]
+        if args.heads:
+            g4 = replace(g4, heads=args.heads)
+        p4 = sg.make_problem(g4)
+        tiles4 = [torch.randn(g4.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g4.n_tiles)]
+        canvas4 = torch.empty(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
+        ms_blend = time_calls(torch, lambda: sg.sg_tile_blend(p4, tiles4, canvas4), 10)
+        blend_bytes = 2.0 * (g4.n_tiles * int(np.prod(g4.tile_shape)) + int(np.prod(g4.grid_shape)))
+        kernels["blend_4k"] = {"ms": round(ms_blend, 4), "GB/s": round(blend_bytes / ms_blend * 1e-6, 1),
+                               "frac_hbm_peak": round(blend_bytes / ms_blend * 1e-6 / PEAK_HBM_GBS, 4)}
+        if args.full:
+            q4, k4, v4 = (torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+            ms4 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4), 2, warmup=1)
+            kernels["step_4k"] = {"ms": round(ms4, 2), "TFLOP/s": round(g4.attention_flops_per_tile * g4.n_tiles / ms4 * 1e-9, 1)}
+            del q4, k4, v4
+        del tiles4, canvas4
+        out["kernels"] = kernels
+        heads = sorted({0, gt.heads - 1, gt.heads // 2})
+        cb, rows, outs = cpu_baseline(torch, gt, x_a[0], 384 if gt.tile_tokens > 10000 else 64, heads)
+        out["cpu_baseline"] = cb
+        # the bench's own sanity check: GPU rows of the last attention launch against the oracle sample
+        got = cache_out[0].reshape(gt.heads, gt.tile_tokens, gt.head_dim)
+        ref = np.stack(outs)
+        gpu = got[heads][:, torch.as_tensor(rows, device="cuda")].to("cpu").to(torch.float64).numpy()
+        out["parity_sample"] = {"max_abs": float(np.abs(gpu - ref).max()),
+                                "rel_l2": float(np.linalg.norm(gpu - ref) / np.linalg.norm(ref))}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -25,9 +25,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #define SG_LDS __attribute__((address_space(3)))
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kQB = 2;                    // 32-query sub-blocks per wavefront
+constexpr int kQB = 1;                    // 32-query sub-blocks per wavefront
 constexpr int kBR = kWaves * kQB * 32;    // 256 query rows per workgroup
 constexpr int kBC = 64;                   // keys per LDS stage
 constexpr int kXcd = 8;
@@ -76,44 +76,57 @@ constexpr int kStageBytes = 2 * kBC * kRowBytes;  // 32 KiB
 __device__ __forceinline__ uint32_t k_slot(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
 __device__ __forceinline__ uint32_t v_slot(int row, int chunk) { return kBC * kRowBytes + row * kRowBytes + ((chunk ^ ((row & 3) << 2)) << 4); }
 
+// Value held by the lane 32 positions away (the other half of the wavefront).
+__device__ __forceinline__ float other_half(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // r[0] = {lo, lo}, r[1] = {hi, hi}
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
 struct Softmax {  // running statistics of one query (replicated in lanes l and l^32)
   float m;        // running max of the raw (unscaled) scores
   float l;        // this lane's share of the running sum
 };
 
-// One 32-key x 32-query block of scores for this lane's query: update (m, l), rescale factor
-// alpha for the output accumulators, and the exponentials packed to bf16 in B-operand order.
+// One 64-key x 32-query block of scores for this lane's query (s[kb][r]: key = key0 + 32*kb +
+// 8*(r>>2) + 4*half + (r&3)): update (m, l), return the rescale factor alpha for the output
+// accumulators and the exponentials packed to bf16 in B-operand order (p[2*kb + h] = registers
+// 8h..8h+7 of sub-block kb).
 template <bool MASK>
-__device__ __forceinline__ float softmax_block(f32x16& s, Softmax& st, const float c /* scale*log2(e) */, const int key0,
-                                               const int n_keys, bf16x8 (&p)[2]) {
+__device__ __forceinline__ float softmax_block(f32x16 (&s)[2], Softmax& st, const float c /* scale*log2(e) */,
+                                               const int key0, const int n_keys, bf16x8 (&p)[4]) {
   const int half = (threadIdx.x & 63) >> 5;
   if (MASK) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int key = key0 + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (key >= n_keys) s[r] = -__builtin_inff();
-    }
-  }
-  float mx = s[0];
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (key >= n_keys) s[kb][r] = -__builtin_inff();
+      }
+  }
+  float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
+  mx = fmaxf(mx, other_half(mx));
   const float m_new = fmaxf(st.m, mx);
   const float mc = m_new * c;
   const float alpha = __builtin_amdgcn_exp2f(st.m * c - mc);  // first block: exp2(-inf) = 0
-  float sum = 0.f;
-  float e[16];
+  float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -mc));
-    sum += e[r];
-  }
-  st.l = st.l * alpha + sum;
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float e[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * h + r], c, -mc));
+#pragma unroll
+      for (int r = 0; r < 8; r += 2) { sum0 += e[r]; sum1 += e[r + 1]; }
+#pragma unroll
+      for (int r = 0; r < 8; ++r) p[2 * kb + h][r] = (__bf16)e[r];
+    }
+  st.l = st.l * alpha + (sum0 + sum1);
   st.m = m_new;
-#pragma unroll
-  for (int h = 0; h < 2; ++h)
-#pragma unroll
-    for (int r = 0; r < 8; ++r) p[h][r] = (__bf16)e[8 * h + r];
   return alpha;
 }
 
@@ -123,7 +136,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
                                                                   const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
                                                                   const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
                                                                   const uint8_t* __restrict__ run_flag) {
-  static_assert(D == 128, "head_dim 128");
+  static_assert(D == 128 && kQB == 1 && kBC == 64, "head_dim 128, one 32-query block per wavefront, 64-key stages");
   if (run_flag && !*run_flag) return;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
@@ -155,24 +168,25 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     for (int kk = 0; kk < D / 16; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, src[2 * kk + half]);
   }
 
-  // ---- K/V loader: thread owns chunk (tid & 15) of rows (tid >> 4) + 16*u, u = 0..3, of every stage
+  // ---- K/V loader: thread owns chunk (tid & 15) of rows (tid >> 4) + kLdRows*u, u < kLdSlots, of every stage
   const int ld_chunk = tid & 15, ld_row = tid >> 4;
-  RowCursor cur[4];
+  constexpr int kLdRows = kThreads / 16, kLdSlots = kBC / kLdRows;
+  RowCursor cur[kLdSlots];
   uint32_t last16;
   {
     const RowCursor cl = cursor_at(vw, N - 1);
     last16 = cl.off16;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)(ld_row + 16 * u) * vw.st16; }
-      else cur[u] = cursor_at(vw, (ld_row + 16 * u < N) ? ld_row + 16 * u : N - 1);
+    for (int u = 0; u < kLdSlots; ++u) {
+      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)(ld_row + kLdRows * u) * vw.st16; }
+      else cur[u] = cursor_at(vw, (ld_row + kLdRows * u < N) ? ld_row + kLdRows * u : N - 1);
     }
   }
-  u32x4 kreg[4], vreg[4];
+  u32x4 kreg[kLdSlots], vreg[kLdSlots];
   auto load_stage = [&](int blk) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int n = blk * kBC + ld_row + 16 * u;
+    for (int u = 0; u < kLdSlots; ++u) {
+      const int n = blk * kBC + ld_row + kLdRows * u;
       const uint32_t off = ((n < N) ? cur[u].off16 : last16) + ld_chunk;
       kreg[u] = kh[off];
       vreg[u] = vh[off];
@@ -183,8 +197,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   auto store_stage = [&](int buf) {
     SG_LDS uint8_t* base = lds + buf * kStageBytes;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = ld_row + 16 * u;
+    for (int u = 0; u < kLdSlots; ++u) {
+      const int row = ld_row + kLdRows * u;
       *(SG_LDS u32x4*)(base + k_slot(row, ld_chunk)) = kreg[u];
       *(SG_LDS u32x4*)(base + v_slot(row, ld_chunk)) = vreg[u];
     }
@@ -210,62 +224,59 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   auto compute = [&](int buf, int blk, auto mask_tag) {
     constexpr bool MASK = decltype(mask_tag)::value;
     const SG_LDS uint8_t* base = lds + buf * kStageBytes;
+    // S^T = K Q^T for the stage's two 32-key sub-blocks: two independent accumulator chains
+    f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < kBC / 32; ++kb) {
-      f32x16 s[kQB];
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
-      const int krow = 32 * kb + lq;
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(base + k_slot(krow, 2 * kk + half)));
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], s[qb], 0, 0, 0);
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(base + k_slot(lq, 2 * kk + half)));
+      const bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(base + k_slot(32 + lq, 2 * kk + half)));
+      if (kk == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[0][kk], zero, 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[0][kk], zero, 0, 0, 0);
+      } else {
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[0][kk], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[0][kk], s[1], 0, 0, 0);
       }
-      bf16x8 p[kQB][2];
+    }
+    bf16x8 p[4];
+    const float alpha = softmax_block<MASK>(s, st[0], c_log2, blk * kBC, N, p);
+    if (__any(alpha != 1.0f)) {
 #pragma unroll
-      for (int qb = 0; qb < kQB; ++qb) {
-        const float alpha = softmax_block<MASK>(s[qb], st[qb], c_log2, blk * kBC + 32 * kb, N, p[qb]);
-        if (__any(alpha != 1.0f)) {
+      for (int db = 0; db < D / 32; ++db) oacc[db][0] *= alpha;
+    }
+    // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d)
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][qb][r] *= alpha;
-        }
-      }
+    for (int ks = 0; ks < 4; ++ks) {  // 16 keys each
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
-#pragma unroll
-        for (int kk2 = 0; kk2 < 2; ++kk2) {
-          const int row0 = 32 * kb + 16 * kk2 + vt_row;
-          const int chunk_byte = 64 * db + vt_dbyte;  // byte offset inside the 256-byte row
-          const uint32_t a0 = v_slot(row0, chunk_byte >> 4) + (chunk_byte & 15);
-          const uint32_t a1 = v_slot(row0 + 8, chunk_byte >> 4) + (chunk_byte & 15);
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a1));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-#pragma unroll
-          for (int qb = 0; qb < kQB; ++qb) oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[qb][kk2], oacc[db][qb], 0, 0, 0);
-        }
+        const int row0 = 16 * ks + vt_row;
+        const int chunk_byte = 64 * db + vt_dbyte;  // byte offset inside the 256-byte row
+        const uint32_t a0 = v_slot(row0, chunk_byte >> 4) + (chunk_byte & 15);
+        const uint32_t a1 = v_slot(row0 + 8, chunk_byte >> 4) + (chunk_byte & 15);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a0));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a1));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[ks], oacc[db][0], 0, 0, 0);
       }
     }
   };
 
+  // Software pipeline over 64-key stages: global loads of stage b+1 are in flight while stage b
+  // is consumed from LDS; the last stage (the only one that can hold keys >= N) is peeled.
   const int n_blocks = (N + kBC - 1) / kBC;
   load_stage(0);
   store_stage(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): Q fragments have landed before the loop starts
   __syncthreads();
-  for (int blk = 0; blk < n_blocks; ++blk) {
-    const bool more = blk + 1 < n_blocks;
-    if (more) load_stage(blk + 1);
-    if (blk == n_blocks - 1 && (N % kBC) != 0) compute(blk & 1, blk, std::true_type{});
-    else compute(blk & 1, blk, std::false_type{});
-    if (more) store_stage((blk + 1) & 1);
+  for (int blk = 0; blk < n_blocks - 1; ++blk) {
+    load_stage(blk + 1);
+    compute(blk & 1, blk, std::false_type{});
+    store_stage((blk + 1) & 1);
     __syncthreads();
   }
+  if ((N % kBC) != 0) compute((n_blocks - 1) & 1, n_blocks - 1, std::true_type{});
+  else compute((n_blocks - 1) & 1, n_blocks - 1, std::false_type{});
 
   // ---- epilogue: O^T accumulators -> packed tile [head][n][d]; lane holds query lq of each sub-block,
   // register r of block db is d = 32*db + 8*(r>>2) + 4*half + (r&3): 4 consecutive d = one 8-byte store
@@ -273,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   for (int qb = 0; qb < kQB; ++qb) {
     const int n = q0 + 32 * qb + lq;
     float l = st[qb].l;
-    l += __shfl_xor(l, 32, 64);
+    l += other_half(l);
     const float inv = 1.0f / l;
     if (n < N) {
       uint16_t* dst = out + ((size_t)head * N + n) * D;
