@@ -8,7 +8,11 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsupergen_tile.so")
-SOURCES = ["sg_api.hip", "attention_bf16.hip", "attention_f32.hip", "blend.hip", "gate.hip"]
+SOURCES = ["sg_api.hip", "attention_bf16.hip", "attention_bf16_generic.hip", "attention_f32.hip", "blend.hip",
+           "gate.hip"]
+# per-file extras: the streaming attention kernel takes row maxima with three-operand max instructions,
+# which the compiler only forms when it need not canonicalise NaNs
+EXTRA = {"attention_bf16.hip": ["-fno-honor-nans"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept out of the generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -30,7 +34,7 @@ def build(verbose=False):
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        msg = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        msg = _run([hipcc, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and msg.strip():
             print(msg, file=sys.stderr)
         return obj

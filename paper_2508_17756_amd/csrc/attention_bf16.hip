@@ -1,17 +1,27 @@
 // Tile attention on the matrix cores (paper Section 2.1 "full attention" over one tile's
 // T x tile_h x tile_w tokens; Section 3: tiles exchange no Q/K/V).
 //
-// Flash-style: a workgroup owns 256 query rows of one head (4 wavefronts x 64 rows) and streams
-// the tile's keys and values through LDS 64 at a time; the N x N score matrix is never stored.
-// All products are bf16 MFMA (32x32x16) with fp32 accumulation, softmax statistics are fp32.
+// Flash-style: a workgroup of 8 wavefronts owns 256 query rows of one head (32 per wavefront) and
+// streams the tile's keys and values through a 4-stage LDS ring, 64 keys per stage, filled by
+// direct global->LDS transfers; the N x N score matrix is never stored.  All products are bf16
+// MFMA (32x32x16) with fp32 accumulation, softmax statistics are fp32.
 //
-// The kernel works on transposed products so that no value ever changes lanes between the two
-// GEMMs:  S^T = K Q^T  puts one query per lane column (lane l holds query l%32, 16 keys in its
-// accumulator registers), so the row max / row sum are in-lane reductions plus one exchange
-// between the two lane halves, and the exponentials, packed to bf16, already sit in the
-// B-operand layout of  O^T = V^T P^T.  V^T fragments come out of LDS through the transposing
-// read (ds_read_b64_tr_b16); K and V rows are stored with XOR-swizzled 16-byte chunks so that
-// both fragment reads are bank-conflict free.
+// Transposed products keep every value in its lane between the two GEMMs:  S^T = K Q^T  puts one
+// query per lane column (lane l holds query l%32, 16 keys of a 32-key block in its accumulator
+// registers), so the exponentials, packed to bf16, already sit in the B-operand layout of
+// O^T = V^T P^T.  V^T fragments come out of LDS through the transposing read (ds_read_b64_tr_b16);
+// K and V rows are stored with XOR-swizzled 16-byte chunks so both fragment reads are free of bank
+// conflicts.
+//
+// The vector ALU, not the matrix pipe, limits this kernel, so the softmax is cut to one exponential,
+// one add and half a convert per score:  Q is pre-multiplied by log2(e)*scale (one bf16 rounding)
+// and the score accumulators start at -M, the softmax reference, so the MFMA result is the
+// exponent itself.  M is an online-softmax running maximum refreshed lazily (see Softmax below).
+// A SIMD overlaps MFMA and vector work only across wavefronts, never inside one, so the two
+// wavefronts of each SIMD run half an iteration apart (see "Schedule" in the kernel).
+//
+// Built with -fno-honor-nans: a NaN in Q, K or V gives unspecified (not necessarily NaN) output.
+#include <type_traits>
 #include "sg_common.h"
 
 namespace sg {
@@ -27,25 +37,21 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kQB = 1;                    // 32-query sub-blocks per wavefront
-constexpr int kBR = kWaves * kQB * 32;    // 256 query rows per workgroup
-constexpr int kBC = 64;                   // keys per LDS stage
+constexpr int kBR = kWaves * 32;   // query rows per workgroup
+constexpr int kBC = 64;            // keys per stage
+constexpr int kStages = 4;
 constexpr int kXcd = 8;
+constexpr int kRowBytes = 256;
+constexpr int kTileBytes = kBC * kRowBytes;          // one K (or V) stage: 16 KiB
+constexpr int kVRegion = kStages * kTileBytes;       // V stages start at 64 KiB
+constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // 128 KiB
 
-// Device-side copy of the tile addressing with 16-byte units (8 bf16) so offsets fit 32 bits.
 struct View16 {
-  uint32_t base16;     // tile origin
-  uint32_t st16;       // 16-byte units per canvas token
-  uint32_t row_skip16; // (W - tw) * st16: jump at the end of a tile row
-  uint32_t frame_skip16; // (H - th) * W * st16: jump at the end of a tile frame
+  uint32_t base16, st16, row_skip16, frame_skip16;
   int32_t th, tw, N;
-  uint32_t head16;     // 16-byte units per head (canvas tensors)
+  uint32_t head16;
 };
-
-struct RowCursor {  // walks tile tokens n, n+kBC, n+2*kBC, ...
-  int32_t i, j;
-  uint32_t off16;
-};
+struct RowCursor { int32_t i, j; uint32_t off16; };
 
 __device__ __forceinline__ RowCursor cursor_at(const View16& vw, int n) {
   const int plane = vw.th * vw.tw;
@@ -53,11 +59,9 @@ __device__ __forceinline__ RowCursor cursor_at(const View16& vw, int n) {
   RowCursor c;
   c.i = r / vw.tw;
   c.j = r - c.i * vw.tw;
-  // canvas token index = (t*H + i)*W + j = n + (t*th + i)*(W - tw) + t*(H - th)*W
   c.off16 = vw.base16 + (uint32_t)n * vw.st16 + (uint32_t)(t * vw.th + c.i) * vw.row_skip16 + (uint32_t)t * vw.frame_skip16;
   return c;
 }
-
 __device__ __forceinline__ void cursor_advance(const View16& vw, RowCursor& c, int step) {
   c.j += step;
   c.off16 += (uint32_t)step * vw.st16;
@@ -68,50 +72,53 @@ __device__ __forceinline__ void cursor_advance(const View16& vw, RowCursor& c, i
   }
 }
 
-// LDS stage: K[64][128] then V[64][128] bf16, rows of 256 bytes = 16 chunks of 16 bytes.
-// K chunk c of row r is stored at chunk c ^ (r & 15); V chunk c of row r at c ^ ((r & 3) << 2).
-constexpr int kRowBytes = 256;
-constexpr int kStageBytes = 2 * kBC * kRowBytes;  // 32 KiB
-
-__device__ __forceinline__ uint32_t k_slot(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
-__device__ __forceinline__ uint32_t v_slot(int row, int chunk) { return kBC * kRowBytes + row * kRowBytes + ((chunk ^ ((row & 3) << 2)) << 4); }
-
-// Value held by the lane 32 positions away (the other half of the wavefront).
-__device__ __forceinline__ float other_half(float x) {
-  const uint32_t u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // r[0] = {lo, lo}, r[1] = {hi, hi}
-  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+// 16 bytes per lane from global memory straight into LDS: lane i fills bytes [16 i, 16 i + 16) of the
+// 1 KiB block at LDS byte address `lds_dst` (wave-uniform).  Address = sbase + voff (32-bit byte offset).
+// Inline assembly keeps the compiler from ordering later LDS reads behind the transfer; completion is
+// awaited explicitly with wait_vmcnt.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N == 0 || N == 4 || N == 8, "");
+  if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+__device__ __forceinline__ void meet() {  // workgroup barrier that nothing is scheduled across
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
 }
 
-struct Softmax {  // running statistics of one query (replicated in lanes l and l^32)
-  float m;        // running max of the raw (unscaled) scores
-  float l;        // this lane's share of the running sum
+// Softmax state of one query (replicated in lanes l and l^32).  Scores leave the MFMA already in the
+// exponent domain: t = log2(e) * scale * <q, k> - M, because Q is pre-multiplied by log2(e) * scale and
+// the accumulator of the first MFMA of each chain starts at -M (M = the reference the exponentials are
+// taken against).  M is an online-softmax running maximum that is refreshed lazily: as long as no
+// exponential of a stage exceeds 2^16 the reference stays, so the common path needs no row maximum, no
+// subtraction and no rescaling of the output accumulators; the result is the same softmax, since any
+// common reference cancels in sum(p v) / sum(p).
+struct Softmax {
+  float M;   // reference, log2 domain
+  float l;   // this lane's share of sum(p)
 };
 
-// One 64-key x 32-query block of scores for this lane's query (s[kb][r]: key = key0 + 32*kb +
-// 8*(r>>2) + 4*half + (r&3)): update (m, l), return the rescale factor alpha for the output
-// accumulators and the exponentials packed to bf16 in B-operand order (p[2*kb + h] = registers
-// 8h..8h+7 of sub-block kb).
-template <bool MASK>
-__device__ __forceinline__ float softmax_block(f32x16 (&s)[2], Softmax& st, const float c /* scale*log2(e) */,
-                                               const int key0, const int n_keys, bf16x8 (&p)[4]) {
+__device__ __forceinline__ void mask_tail(f32x16 (&t)[2], const int key0, const int n_keys) {
   const int half = (threadIdx.x & 63) >> 5;
-  if (MASK) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (key >= n_keys) s[kb][r] = -__builtin_inff();
-      }
-  }
-  float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s[0][r], s[1][r]));
-  mx = fmaxf(mx, other_half(mx));
-  const float m_new = fmaxf(st.m, mx);
-  const float mc = m_new * c;
-  const float alpha = __builtin_amdgcn_exp2f(st.m * c - mc);  // first block: exp2(-inf) = 0
+    for (int r = 0; r < 16; ++r) {
+      const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (key >= n_keys) t[kb][r] = -__builtin_inff();
+    }
+}
+
+// p[2 kb + h] = bf16(exp2(t[kb][8h..8h+7])) in B-operand order; returns this lane's sum of the exponentials
+__device__ __forceinline__ float exp_block(const f32x16 (&t)[2], bf16x8 (&p)[4]) {
   float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
@@ -119,16 +126,28 @@ __device__ __forceinline__ float softmax_block(f32x16 (&s)[2], Softmax& st, cons
     for (int h = 0; h < 2; ++h) {
       float e[8];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) e[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][8 * h + r], c, -mc));
-#pragma unroll
-      for (int r = 0; r < 8; r += 2) { sum0 += e[r]; sum1 += e[r + 1]; }
+      for (int r = 0; r < 8; ++r) e[r] = __builtin_amdgcn_exp2f(t[kb][8 * h + r]);
 #pragma unroll
       for (int r = 0; r < 8; ++r) p[2 * kb + h][r] = (__bf16)e[r];
+#pragma unroll
+      for (int r = 0; r < 8; r += 2) { sum0 += e[r]; sum1 += e[r + 1]; }
     }
-  st.l = st.l * alpha + (sum0 + sum1);
-  st.m = m_new;
-  return alpha;
+  return sum0 + sum1;
 }
+// row maximum of the stage for this lane's query, combined over both halves of the wavefront
+__device__ __forceinline__ float block_max(const f32x16 (&t)[2]) {
+  float mx0 = t[0][0], mx1 = t[1][0];
+#pragma unroll
+  for (int r = 1; r < 15; r += 2) {
+    mx0 = fmaxf(fmaxf(mx0, t[0][r]), t[0][r + 1]);
+    mx1 = fmaxf(fmaxf(mx1, t[1][r]), t[1][r + 1]);
+  }
+  const float mx = fmaxf(fmaxf(mx0, t[0][15]), fmaxf(mx1, t[1][15]));
+  const uint32_t mu = __float_as_uint(mx);
+  const auto sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+constexpr float kOverflowGuard = 65536.0f;   // a stage's exponentials may grow to 2^16 before the reference moves
 
 template <int D, bool LINEAR>
 __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 vw, const float c_log2, const int heads,
@@ -136,156 +155,324 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
                                                                   const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
                                                                   const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
                                                                   const uint8_t* __restrict__ run_flag) {
-  static_assert(D == 128 && kQB == 1 && kBC == 64, "head_dim 128, one 32-query block per wavefront, 64-key stages");
+  static_assert(D == 128, "head_dim 128");
   if (run_flag && !*run_flag) return;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD walks a contiguous
-  // range of (head, query block) pairs and its 32 CUs stream the same head's K/V through one L2.
+  // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD walks a contiguous range
+  // of (head, query block) pairs and its CUs stream the same head's K/V through one L2.
   const int xcd = blockIdx.x % kXcd, slot = blockIdx.x / kXcd;
   const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= heads * n_qblocks) return;
+  if (logical >= heads * n_qblocks) return;
   const int head = logical / n_qblocks, qblk = logical - head * n_qblocks;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, half = lane >> 5;
   const int N = vw.N;
   const uint32_t head_off16 = (uint32_t)head * vw.head16;
-  const u32x4* __restrict__ kh = kg + head_off16;
-  const u32x4* __restrict__ vh = vg + head_off16;
+  const u32x4* const kh = kg + head_off16;   // wave-uniform bases of this head
+  const u32x4* const vh = vg + head_off16;
 
-  // ---- Q fragments (B operand of S^T = K Q^T): query = q0 + 32*qb + lq, d = 16*kk + 8*half + 0..7
-  const int q0 = qblk * kBR + wave * (kQB * 32);
-  bf16x8 qf[kQB][D / 16];
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    int n = q0 + 32 * qb + lq;
+  // ---- Q fragments (B operand of S^T = K Q^T): query q0 + lq, d = 16 kk + 8 half + 0..7
+  const int q0 = qblk * kBR + wave * 32;
+  bf16x8 qf[D / 16];
+  {
+    int n = q0 + lq;
     if (n > N - 1) n = N - 1;
     const RowCursor cq = cursor_at(vw, n);
     const u32x4* src = qg + head_off16 + cq.off16;
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, src[2 * kk + half]);
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const u32x4 raw = src[2 * kk + half];
+      u32x4 scaled;   // q * log2(e) * scale, rounded to bf16 once
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        scaled[e] = pack_bf16x2(bf16_bits_to_f32(raw[e] & 0xffffu) * c_log2, __uint_as_float(raw[e] & 0xffff0000u) * c_log2);
+      qf[kk] = __builtin_bit_cast(bf16x8, scaled);
+    }
   }
 
-  // ---- K/V loader: thread owns chunk (tid & 15) of rows (tid >> 4) + kLdRows*u, u < kLdSlots, of every stage
-  const int ld_chunk = tid & 15, ld_row = tid >> 4;
-  constexpr int kLdRows = kThreads / 16, kLdSlots = kBC / kLdRows;
-  RowCursor cur[kLdSlots];
+  // ---- LDS layout: K stages [4][64 rows][256 B] at 0, V stages at 64 KiB.  16-byte chunk c of K row r
+  // sits at chunk c ^ (r & 15); chunk c of V row r at c ^ ((r & 3) << 2): both fragment reads below are
+  // then bank-conflict free.  All per-lane addresses are fixed; stage and sub-block enter as immediates.
+  uint32_t kaddr[D / 16];   // A operand of QK: key row lq (+32), chunk 2 kk + half
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) kaddr[kk] = lds0 + lq * kRowBytes + (((2 * kk + half) ^ (lq & 15)) << 4);
+  // V^T fragments through the transposing read: within a 16-lane group lane s reads 4 consecutive d of key
+  // row (s >> 2); the hardware hands lane i the 4 keys of d column i.
+  const int grp = lane >> 4, gi = lane & 15;
+  const int vt_row = 4 * (grp >> 1) + (gi >> 2);
+  const int vt_dbyte = (16 * (grp & 1) + 4 * (gi & 3)) * 2;
+  uint32_t vaddr[D / 32];   // + 4096 ks (+ 2048 for keys +8), d block db
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+    vaddr[db] = lds0 + kVRegion + vt_row * kRowBytes + (((4 * db + (vt_dbyte >> 4)) ^ ((vt_row & 3) << 2)) << 4) + (vt_dbyte & 15);
+
+  // ---- DMA loader: wavefront w moves rows 8w..8w+7 of every stage, 4 rows (1 KiB) per instruction; lane l
+  // fills chunk slot (l & 15) of row 8w + 4u + (l >> 4) and therefore fetches the chunk that belongs there.
+  const int ld_sub = lane >> 4, ld_slot = lane & 15;
+  RowCursor cur[2];
+  uint32_t kchunk[2], vchunk[2];
+  uint32_t koff[2], voff[2];   // byte offsets from kh / vh of the next stage to issue
   uint32_t last16;
   {
-    const RowCursor cl = cursor_at(vw, N - 1);
-    last16 = cl.off16;
+    last16 = cursor_at(vw, N - 1).off16;
 #pragma unroll
-    for (int u = 0; u < kLdSlots; ++u) {
-      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)(ld_row + kLdRows * u) * vw.st16; }
-      else cur[u] = cursor_at(vw, (ld_row + kLdRows * u < N) ? ld_row + kLdRows * u : N - 1);
+    for (int u = 0; u < 2; ++u) {
+      const int row = 8 * wave + 4 * u + ld_sub;
+      kchunk[u] = ld_slot ^ (row & 15);
+      vchunk[u] = ld_slot ^ ((row & 3) << 2);
+      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)row * vw.st16; }
+      else cur[u] = cursor_at(vw, row < N ? row : N - 1);
+      koff[u] = (cur[u].off16 + kchunk[u]) << 4;
+      voff[u] = (cur[u].off16 + vchunk[u]) << 4;
     }
   }
-  u32x4 kreg[kLdSlots], vreg[kLdSlots];
-  auto load_stage = [&](int blk) {
+  const uint32_t dma_dst = lds0 + wave * (8 * kRowBytes);
+  // issue stage `blk` (all of its rows below N) into ring slot `st`; advance to the next stage
+  auto issue_full = [&](int blk, int st) {
 #pragma unroll
-    for (int u = 0; u < kLdSlots; ++u) {
-      const int n = blk * kBC + ld_row + kLdRows * u;
-      const uint32_t off = ((n < N) ? cur[u].off16 : last16) + ld_chunk;
-      kreg[u] = kh[off];
-      vreg[u] = vh[off];
-      if (LINEAR) cur[u].off16 += kBC * vw.st16;
-      else if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+    for (int u = 0; u < 2; ++u) {
+      dma16(kh, koff[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+      dma16(vh, voff[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+      if (LINEAR) {
+        koff[u] += (kBC * 16) * vw.st16;
+        voff[u] += (kBC * 16) * vw.st16;
+      } else {
+        const int n = blk * kBC + 8 * wave + 4 * u + ld_sub;
+        if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+        koff[u] = (cur[u].off16 + kchunk[u]) << 4;
+        voff[u] = (cur[u].off16 + vchunk[u]) << 4;
+      }
     }
   };
-  auto store_stage = [&](int buf) {
-    SG_LDS uint8_t* base = lds + buf * kStageBytes;
+  // same for a stage that may hold rows >= N: those lanes fetch the last valid row (masked later)
+  auto issue_any = [&](int blk, int st) {
 #pragma unroll
-    for (int u = 0; u < kLdSlots; ++u) {
-      const int row = ld_row + kLdRows * u;
-      *(SG_LDS u32x4*)(base + k_slot(row, ld_chunk)) = kreg[u];
-      *(SG_LDS u32x4*)(base + v_slot(row, ld_chunk)) = vreg[u];
+    for (int u = 0; u < 2; ++u) {
+      const int n = blk * kBC + 8 * wave + 4 * u + ld_sub;
+      const uint32_t ko = (n < N) ? koff[u] : ((last16 + kchunk[u]) << 4);
+      const uint32_t vo = (n < N) ? voff[u] : ((last16 + vchunk[u]) << 4);
+      dma16(kh, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+      dma16(vh, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+      if (LINEAR) {
+        koff[u] += (kBC * 16) * vw.st16;
+        voff[u] += (kBC * 16) * vw.st16;
+      } else {
+        if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+        koff[u] = (cur[u].off16 + kchunk[u]) << 4;
+        voff[u] = (cur[u].off16 + vchunk[u]) << 4;
+      }
     }
   };
 
-  f32x16 oacc[D / 32][kQB];
+  f32x16 oacc[D / 32];
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb)
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  Softmax sm;
+  sm.M = 0.f;
+  sm.l = 0.f;
+  f32x16 cinit;   // accumulator start of every score chain: -M in all registers
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][qb][r] = 0.f;
-  Softmax st[kQB];
+  for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
+
+  auto kfrag = [&](int kk, int kb, int off) -> bf16x8 {
+    return __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(uintptr_t)(kaddr[kk] + off + kb * (32 * kRowBytes)));
+  };
+  auto vfrag = [&](int ks, int db, int off) -> bf16x8 {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(uintptr_t)(vaddr[db] + off + ks * (16 * kRowBytes)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(uintptr_t)(vaddr[db] + off + ks * (16 * kRowBytes) + 8 * kRowBytes));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  };
+  // S^T = K Q^T of the stage at LDS byte offset `off`: two independent accumulator chains, fragment reads
+  // issued two steps ahead of the MFMAs that consume them
+  constexpr int kPF = 2;
+  auto qk = [&](int off, f32x16 (&s)[2]) {
+    bf16x8 a[D / 16][2];
 #pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) { st[qb].m = -__builtin_inff(); st[qb].l = 0.f; }
-
-  // V^T fragment addressing for the transposing read: within a 16-lane group, lane s reads 4
-  // consecutive d of key row (s >> 2); the hardware hands lane i the 4 keys of d column i.
-  const int grp = lane >> 4, gi = lane & 15;
-  const int vt_row = 4 * (grp >> 1) + (gi >> 2);        // + 32*kb + 16*kk2 (+8 for the second read)
-  const int vt_dbyte = (16 * (grp & 1) + 4 * (gi & 3)) * 2;  // + 64*db bytes
-
-  auto compute = [&](int buf, int blk, auto mask_tag) {
-    constexpr bool MASK = decltype(mask_tag)::value;
-    const SG_LDS uint8_t* base = lds + buf * kStageBytes;
-    // S^T = K Q^T for the stage's two 32-key sub-blocks: two independent accumulator chains
-    f32x16 s[2];
+    for (int kk = 0; kk < kPF; ++kk) { a[kk][0] = kfrag(kk, 0, off); a[kk][1] = kfrag(kk, 1, off); }
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) {
-      const bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(base + k_slot(lq, 2 * kk + half)));
-      const bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(base + k_slot(32 + lq, 2 * kk + half)));
+      if (kk + kPF < D / 16) { a[kk + kPF][0] = kfrag(kk + kPF, 0, off); a[kk + kPF][1] = kfrag(kk + kPF, 1, off); }
+      __builtin_amdgcn_sched_barrier(0);
       if (kk == 0) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[0][kk], zero, 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[0][kk], zero, 0, 0, 0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[kk], cinit, 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[kk], cinit, 0, 0, 0);
       } else {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[0][kk], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[0][kk], s[1], 0, 0, 0);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[kk], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[kk], s[1], 0, 0, 0);
       }
-    }
-    bf16x8 p[4];
-    const float alpha = softmax_block<MASK>(s, st[0], c_log2, blk * kBC, N, p);
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db) oacc[db][0] *= alpha;
-    }
-    // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {  // 16 keys each
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db) {
-        const int row0 = 16 * ks + vt_row;
-        const int chunk_byte = 64 * db + vt_dbyte;  // byte offset inside the 256-byte row
-        const uint32_t a0 = v_slot(row0, chunk_byte >> 4) + (chunk_byte & 15);
-        const uint32_t a1 = v_slot(row0 + 8, chunk_byte >> 4) + (chunk_byte & 15);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a0));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(base + a1));
-        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), p[ks], oacc[db][0], 0, 0, 0);
-      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-
-  // Software pipeline over 64-key stages: global loads of stage b+1 are in flight while stage b
-  // is consumed from LDS; the last stage (the only one that can hold keys >= N) is peeled.
-  const int n_blocks = (N + kBC - 1) / kBC;
-  load_stage(0);
-  store_stage(0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): Q fragments have landed before the loop starts
-  __syncthreads();
-  for (int blk = 0; blk < n_blocks - 1; ++blk) {
-    load_stage(blk + 1);
-    compute(blk & 1, blk, std::false_type{});
-    store_stage((blk + 1) & 1);
-    __syncthreads();
-  }
-  if ((N % kBC) != 0) compute((n_blocks - 1) & 1, n_blocks - 1, std::true_type{});
-  else compute((n_blocks - 1) & 1, n_blocks - 1, std::false_type{});
-
-  // ---- epilogue: O^T accumulators -> packed tile [head][n][d]; lane holds query lq of each sub-block,
-  // register r of block db is d = 32*db + 8*(r>>2) + 4*half + (r&3): 4 consecutive d = one 8-byte store
+  // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d)
+  auto pv = [&](int off, const bf16x8 (&pp)[4]) {
+    bf16x8 a[16];
 #pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) {
-    const int n = q0 + 32 * qb + lq;
-    float l = st[qb].l;
-    l += other_half(l);
-    const float inv = 1.0f / l;
+    for (int i = 0; i < 2 * kPF; ++i) a[i] = vfrag(i >> 2, i & 3, off);
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      if (i + 2 * kPF < 16) {
+        a[i + 2 * kPF] = vfrag((i + 2 * kPF) >> 2, (i + 2 * kPF) & 3, off);
+        a[i + 2 * kPF + 1] = vfrag((i + 2 * kPF + 1) >> 2, (i + 2 * kPF + 1) & 3, off);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], pp[i >> 2], oacc[i & 3], 0, 0, 0);
+      oacc[(i + 1) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i + 1], pp[(i + 1) >> 2], oacc[(i + 1) & 3], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  f32x16 s[2];   // scores of the stage in flight between an MFMA phase and the next softmax phase
+  // softmax phase of one stage: scores t (exponent domain) -> p, l.  The exponentials are taken against the
+  // current reference; if one of them outgrew the guard (or on the first stage, which sets the reference) the
+  // reference moves by delta per query: scores, running sum and output accumulators are brought to the new
+  // reference and the exponentials are retaken.  One copy of the code, looped at most twice.
+  auto softmax_phase = [&](int key0, bool masked, bool first, bf16x8 (&p)[4]) {
+    if (masked) mask_tail(s, key0, N);
+    bool move = first;
+    float sum;
+#pragma nounroll
+    for (;;) {
+      if (move) {
+        const float mx = block_max(s);
+        const float delta = first ? mx : fmaxf(mx, 0.f);
+        const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) s[kb] -= delta;
+        sm.M += delta;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cinit[r] = -sm.M;
+        sm.l *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) oacc[db] *= alpha;
+      }
+      sum = exp_block(s, p);
+      if (move || !__any(!(sum < kOverflowGuard))) break;
+      move = true;
+    }
+    sm.l += sum;
+  };
+
+  // ---- Schedule.  Wavefronts 0-3 (group 0) and 4-7 (group 1) share the four SIMDs pairwise and run half an
+  // iteration apart, so that while one wavefront of a SIMD feeds the matrix pipe (MFMA phase: PV(k), QK(k+1))
+  // the other works the vector ALU (softmax phase).  One workgroup barrier B_k per iteration re-establishes
+  // the offset: after it group 0 starts MFMA phase k (its softmax k ran before the barrier) while group 1
+  // starts softmax k followed by MFMA phase k.
+  // Ring of 4 stages: between B_k and B_k+1 both groups read V of stage k and K of stage k+1; stage k+3 is
+  // issued right after B_k into the slot of stage k-1 (last read before B_k) and must have landed by B_k+2.
+  const int n_blocks = (N + kBC - 1) / kBC;
+  const bool tail = (N % kBC) != 0;
+  const int grp1 = __builtin_amdgcn_readfirstlane(wave >> 2);
+  auto wait_stage = [&](int younger_stages) {   // own transfers: all but the youngest `younger_stages` stages landed
+    __builtin_amdgcn_sched_barrier(0);
+    if (younger_stages >= 2) wait_vmcnt<8>();
+    else if (younger_stages == 1) wait_vmcnt<4>();
+    else wait_vmcnt<0>();
+  };
+  bf16x8 p[4];
+  auto mfma_phase_static = [&](auto st_tag) {
+    constexpr int ST = decltype(st_tag)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+    pv(ST * kTileBytes, p);
+    qk(((ST + 1) % kStages) * kTileBytes, s);
+    asm volatile("" : : "v"(s[0]), "v"(s[1]));
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto mfma_phase_any = [&](int k) {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+    pv((k % kStages) * kTileBytes, p);
+    if (k + 1 < n_blocks) qk(((k + 1) % kStages) * kTileBytes, s);
+    asm volatile("" : : "v"(s[0]), "v"(s[1]));
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto softmax_pinned = [&](int j, bool masked, bool first) {
+    softmax_phase(j * kBC, masked, first, p);
+    asm volatile("" : : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(sm.l), "v"(cinit));
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  for (int b = 0; b < 3; ++b)
+    if (b < n_blocks) issue_any(b, b);
+  wait_stage(n_blocks >= 3 ? 2 : (n_blocks == 2 ? 1 : 0));
+  meet();
+  qk(0, s);
+  asm volatile("" : : "v"(s[0]), "v"(s[1]));
+  const int n_steady = (n_blocks >= 2 * kStages) ? kStages + ((n_blocks - 2 * kStages) / kStages) * kStages : 0;
+
+  if (!grp1) {
+    softmax_pinned(0, tail && n_blocks == 1, true);
+    wait_stage(n_blocks >= 3 ? 1 : 0);
+    meet();   // B_0
+    auto general = [&](int k) {
+      if (k + 3 < n_blocks) issue_any(k + 3, (k + 3) % kStages);
+      mfma_phase_any(k);
+      if (k + 1 < n_blocks) softmax_pinned(k + 1, tail && k + 1 == n_blocks - 1, false);
+      wait_stage(k + 3 <= n_blocks - 1 ? 1 : 0);
+      meet();
+    };
+    auto steady = [&](int k, auto st_tag) {
+      constexpr int ST = decltype(st_tag)::value;
+      issue_full(k + 3, (ST + 3) % kStages);
+      mfma_phase_static(st_tag);
+      softmax_pinned(k + 1, false, false);
+      wait_stage(1);
+      meet();
+    };
+    int k = 0;
+    for (; k < kStages && k < n_blocks; ++k) general(k);
+    for (; k < n_steady; k += kStages) {
+      steady(k, std::integral_constant<int, 0>{});
+      steady(k + 1, std::integral_constant<int, 1>{});
+      steady(k + 2, std::integral_constant<int, 2>{});
+      steady(k + 3, std::integral_constant<int, 3>{});
+    }
+    for (; k < n_blocks; ++k) general(k);
+  } else {
+    wait_stage(n_blocks >= 3 ? 1 : 0);
+    meet();   // B_0
+    auto general = [&](int k) {
+      if (k + 3 < n_blocks) issue_any(k + 3, (k + 3) % kStages);
+      softmax_pinned(k, tail && k == n_blocks - 1, k == 0);
+      mfma_phase_any(k);
+      wait_stage(k + 3 <= n_blocks - 1 ? 1 : 0);
+      meet();
+    };
+    auto steady = [&](int k, auto st_tag) {
+      constexpr int ST = decltype(st_tag)::value;
+      issue_full(k + 3, (ST + 3) % kStages);
+      softmax_pinned(k, false, false);
+      mfma_phase_static(st_tag);
+      wait_stage(1);
+      meet();
+    };
+    int k = 0;
+    for (; k < kStages && k < n_blocks; ++k) general(k);
+    for (; k < n_steady; k += kStages) {
+      steady(k, std::integral_constant<int, 0>{});
+      steady(k + 1, std::integral_constant<int, 1>{});
+      steady(k + 2, std::integral_constant<int, 2>{});
+      steady(k + 3, std::integral_constant<int, 3>{});
+    }
+    for (; k < n_blocks; ++k) general(k);
+  }
+
+  // ---- epilogue: O^T accumulators -> packed tile [head][n][d]; register r of block db is
+  // d = 32 db + 8 (r>>2) + 4 half + (r&3): 4 consecutive d = one 8-byte store
+  {
+    const int n = q0 + lq;
+    const uint32_t lu = __float_as_uint(sm.l);
+    const auto sw = __builtin_amdgcn_permlane32_swap(lu, lu, false, false);
+    const float inv = 1.0f / (__uint_as_float(sw[0]) + __uint_as_float(sw[1]));
     if (n < N) {
       uint16_t* dst = out + ((size_t)head * N + n) * D;
 #pragma unroll
@@ -293,8 +480,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           u32x2 w;
-          w[0] = pack_bf16x2(oacc[db][qb][4 * g] * inv, oacc[db][qb][4 * g + 1] * inv);
-          w[1] = pack_bf16x2(oacc[db][qb][4 * g + 2] * inv, oacc[db][qb][4 * g + 3] * inv);
+          w[0] = pack_bf16x2(oacc[db][4 * g] * inv, oacc[db][4 * g + 1] * inv);
+          w[1] = pack_bf16x2(oacc[db][4 * g + 2] * inv, oacc[db][4 * g + 3] * inv);
           *(u32x2*)(dst + 32 * db + 8 * g + 4 * half) = w;
         }
     }
@@ -306,6 +493,10 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
                           const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
   if (head_dim != 128) return SG_ERR_UNSUPPORTED;
+  // The streaming loads address a head's K/V with 32-bit byte offsets from a wave-uniform base; canvases
+  // whose per-head extent does not fit take the kernel with 64-bit addressing.
+  const int64_t head_extent = ((int64_t)tv.T * tv.H * tv.W) * tv.stride_token + tv.base;
+  if (head_extent * 2 >= (1ll << 32)) return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
   View16 vw;
   vw.base16 = (uint32_t)(tv.base / 8);
   vw.st16 = (uint32_t)(tv.stride_token / 8);
@@ -318,18 +509,18 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   const int total = n_qblocks * heads;
   const int per_xcd = (total + kXcd - 1) / kXcd;
   const float c_log2 = scale * 1.4426950408889634f;
-  const size_t lds = 2 * kStageBytes;
   dim3 grid(per_xcd * kXcd);
+  static bool attr_set[2] = {false, false};
   if (linear) {
     auto kern = attention_bf16_kernel<128, true>;
-    SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                     (const u32x4*)v, (uint16_t*)out, run_flag);
+    if (!attr_set[0]) { SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)); attr_set[0] = true; }
+    kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
+                                           (const u32x4*)v, (uint16_t*)out, run_flag);
   } else {
     auto kern = attention_bf16_kernel<128, false>;
-    SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                     (const u32x4*)v, (uint16_t*)out, run_flag);
+    if (!attr_set[1]) { SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)); attr_set[1] = true; }
+    kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
+                                           (const u32x4*)v, (uint16_t*)out, run_flag);
   }
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;

@@ -72,6 +72,27 @@ def test_attention_bf16_token_major_layout():
     assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv_hm, 1, 1), "bf16")
 
 
+def test_attention_bf16_wide_token_stride_takes_general_addressing():
+    """A canvas whose per-head extent exceeds 4 GiB (token stride of 2^20 elements) is served by the
+    kernel with 64-bit addressing; same numbers as the oracle."""
+    g = _geom("wide", 2, 32, 40, 16, 20, 16, 20, 1, 128, "bf16", 71)        # 2560 canvas tokens, N = 640
+    stride = 1 << 20
+    dense = canvas_qkv(g)
+    wide = []
+    for t in dense:
+        buf = torch.empty(g.grid_tokens * stride, dtype=torch.bfloat16, device="cuda")
+        view = buf.as_strided((g.grid_tokens, g.head_dim), (stride, 1))
+        view.copy_(t.reshape(g.grid_tokens, g.head_dim))
+        wide.append(buf)
+    p = sg.make_problem(g)
+    p.grid_stride_token = stride
+    p.grid_stride_head = 128                      # one head; any positive multiple of 8
+    assert sg.sg_problem_validate(p) == sg.SG_OK
+    out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
+    sg.sg_tile_attention(p, *wide, 1, 1, out)
+    assert_close(to_f64(out), oracle_tile_attention_full(g, *dense, 1, 1), "bf16")
+
+
 def test_attention_bf16_large_logits_and_constant_v():
     """Scores far from N(0,1): softmax concentrates; constant V must come back exactly-ish."""
     g = _geom("sharp", 2, 10, 16, 10, 16, 10, 16, 2, 128, "bf16", 41)
