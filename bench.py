@@ -9,8 +9,10 @@ between two inputs 0.1-noise apart, so the gate always orders a recompute and no
 skipped.  `value` = attention FLOPs (4 N^2 d heads, true N) / step time.
 
 Prints ONE JSON line.  Extra objects: `roofline` (the attention kernel alone, timed with HIP
-events on its stream), `kernels` (blend and gate GB/s at the 4K sizes, 4K step ms when
---full), `cpu_baseline` (the fp64 oracle on a bounded row sample, host cores).
+events on its stream; `traffic` = HBM bytes per launch from the committed rocprofv3 counter
+summary, if present), `kernels` (gate and blend GB/s at the 4K sizes, the 4K canvas step of
+20 tile attentions + blend in ms; with --full also the 2K canvas step and the gated 10-step
+run), `cpu_baseline` (the fp64 oracle on a bounded row sample, host cores).
 """
 import argparse
 import json
@@ -44,6 +46,23 @@ def time_calls(torch, fn, reps, warmup=1):
     return e0.elapsed_time(e1) / reps      # ms per call
 
 
+def counter_summary(name):
+    """key = value lines of a committed rocprofv3 counter summary under profiles/ (None if absent)."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                try:
+                    vals[k.strip()] = float(v.split()[0])
+                except (ValueError, IndexError):
+                    pass
+    return vals
+
+
 def build_tile_inputs(torch, g, n_tiles, seed):
     """Per-tile packed [3][heads][T][th][tw][d] inputs, N(0,1) bf16, generated on the device."""
     from synthetic import randn_tensor
@@ -71,6 +90,58 @@ def cpu_baseline(torch, g, x, rows_per_head, heads):
             }, rows, outs
 
 
+def full_extras(torch, sg, args):
+    """2K canvas step (9 tile attentions of 80,640 tokens + blend) and the gated 10-step 4K run."""
+    from dataclasses import replace
+    from synthetic import CONFIGS, eps_table, perturb_, randn_tensor
+    res = {}
+    g3 = CONFIGS["canvas2k_bf16"]
+    if args.heads:
+        g3 = replace(g3, heads=args.heads)
+    p3 = sg.make_problem(g3)
+    q3, k3, v3 = (torch.randn(g3.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    tiles3 = [torch.empty(g3.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g3.n_tiles)]
+    canvas3 = torch.empty(g3.grid_shape, dtype=torch.bfloat16, device="cuda")
+    ms3 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p3, canvas3, tiles3, q=q3, k=k3, v=v3), 2, warmup=1)
+    res["step_2k"] = {"ms": round(ms3, 2), "tiles": g3.n_tiles,
+                      "TFLOP/s": round(g3.attention_flops_per_tile * g3.n_tiles / ms3 * 1e-9, 1)}
+    ms_b3 = time_calls(torch, lambda: sg.sg_tile_blend(p3, tiles3, canvas3), 20)
+    nb3 = 2.0 * (g3.n_tiles * int(np.prod(g3.tile_shape)) + int(np.prod(g3.grid_shape)))
+    res["blend_2k"] = {"ms": round(ms_b3, 4), "GB/s": round(nb3 / ms_b3 * 1e-6, 1),
+                       "frac_hbm_peak": round(nb3 / ms_b3 * 1e-6 / PEAK_HBM_GBS, 4)}
+    del q3, k3, v3, tiles3, canvas3
+    # gated run: per-tile inputs drift by eps in {0.01, 0.1}; the gate recomputes the 0.1 tiles
+    g5 = CONFIGS["canvas4k_gate_bf16"]
+    if args.heads:
+        g5 = replace(g5, heads=args.heads)
+    p5 = sg.make_problem(g5)
+    n5 = g5.n_tiles
+    tile_x = [randn_tensor((3,) + g5.tile_shape, "bf16", g5.seed + i, device="cuda") for i in range(n5)]
+    cache_x = [torch.zeros_like(t) for t in tile_x]
+    cache_out = [torch.zeros(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
+    has_cache = torch.zeros(n5, dtype=torch.uint8, device="cuda")
+    scores = torch.zeros(n5, dtype=torch.float32, device="cuda")
+    rec = torch.zeros(n5, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n5), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(g5.grid_shape, dtype=torch.bfloat16, device="cuda")
+    eps = eps_table(g5.seed + 1000, g5.steps, n5)
+    per_step = []
+    for k in range(g5.steps):
+        if k:
+            for i in range(n5):
+                perturb_(tile_x[i], eps[k, i], g5.seed + 100 * k + i)
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch)
+        e0.record()
+        sg.sg_denoise_step_tiled(p5, canvas, cache_out, tile_x=tile_x, cache_x=cache_x, has_cache=has_cache,
+                                 threshold=g5.threshold, scores=scores, recompute=rec, workspace=ws)
+        e1.record()
+        e1.synchronize()
+        per_step.append({"ms": round(e0.elapsed_time(e1), 2), "recomputed": int(rec.sum())})
+    res["gated_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1), "steps": per_step}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,11 +150,14 @@ def main():
     ap.add_argument("--workload", default="tile720p_bf16")
     ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
     ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
-    ap.add_argument("--full", action="store_true", help="also time the 4K canvas step (20 tile attentions + blend)")
+    ap.add_argument("--full", action="store_true", help="also time the 2K canvas step and the gated 10-step 4K run")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="query rows per head of the CPU baseline sample")
+    ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the CPU baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus %d is not supported "
-              "(tiles would shard across GPUs as described in DESIGN.md)" % args.gpus, file=sys.stderr)
+              "(tiles are independent and would be dealt to the GPUs, but no multi-GPU path is built)" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -150,6 +224,10 @@ def main():
 
     ms_att = time_calls(torch, att, max(2, args.steps))
     att_tflops = gt.attention_flops_per_tile / (ms_att * 1e-3) * 1e-12
+    pmc = counter_summary("attention_bf16_tile720p_hbm_traffic.txt")
+    traffic = None
+    if pmc and "hbm_bytes_per_launch" in pmc and not args.heads and g.name == "tile720p_bf16":
+        traffic = pmc["hbm_bytes_per_launch"]
     out = {
         "metric": "tile-attention TFLOP/s (% bf16 MFMA peak) + 4K tiled denoise-step ms",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -160,7 +238,7 @@ def main():
         "pct_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "host_ms_per_step": round(wall_ms, 3),
         "roofline": {"bound": "mfma", "achieved": round(att_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                      "kernel": "attention_bf16_kernel", "ms_per_launch": round(ms_att, 3),
                      "flops_per_launch": gt.attention_flops_per_tile},
     }
@@ -169,33 +247,43 @@ def main():
 
     if not args.no_extras:
         kernels = {}
-        # cache gate alone at this workload's sizes: reads x_cur and x_cached once
+        hbm = lambda nbytes, ms: {"ms": round(ms, 4), "GB/s": round(nbytes / ms * 1e-6, 1),
+                                  "frac_hbm_peak": round(nbytes / ms * 1e-6 / PEAK_HBM_GBS, 4)}
+        # cache gate alone on this workload's tile: reads x_cur and x_cached once
         has_all = torch.ones(n, dtype=torch.uint8, device="cuda")
-        ms_gate = time_calls(torch, lambda: sg.sg_cache_gate(x_b, x_a, has_all, 0.05, scores, rec, ws), 10)
-        gate_bytes = 2.0 * 3 * E * 2 * n
-        kernels["gate"] = {"ms": round(ms_gate, 4), "GB/s": round(gate_bytes / ms_gate * 1e-6, 1),
-                           "frac_hbm_peak": round(gate_bytes / ms_gate * 1e-6 / PEAK_HBM_GBS, 4), "tiles": n}
+        ms_gate = time_calls(torch, lambda: sg.sg_cache_gate(x_b, x_a, has_all, 0.05, scores, rec, ws), 20)
+        kernels["gate_1tile"] = dict(hbm(2.0 * 3 * E * 2 * n, ms_gate), tiles=n)
         del x_b, cache_x
         # blend and gate at the 4K sizes (20 tiles of 75,600 tokens into a 21x135x240 canvas)
         g4 = CONFIGS["canvas4k_bf16"]
         if args.heads:
             g4 = replace(g4, heads=args.heads)
         p4 = sg.make_problem(g4)
-        tiles4 = [torch.randn(g4.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g4.n_tiles)]
+        n4, E4 = g4.n_tiles, int(np.prod(g4.tile_shape))
+        cur4 = [torch.randn(3 * E4, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
+        old4 = [torch.randn(3 * E4, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
+        has4 = torch.ones(n4, dtype=torch.uint8, device="cuda")
+        sc4 = torch.empty(n4, dtype=torch.float32, device="cuda")
+        rc4 = torch.empty(n4, dtype=torch.uint8, device="cuda")
+        ws4 = torch.empty(sg.sg_workspace_bytes(n4), dtype=torch.uint8, device="cuda")
+        ms_gate4 = time_calls(torch, lambda: sg.sg_cache_gate(cur4, old4, has4, 0.05, sc4, rc4, ws4), 10)
+        kernels["gate_4k"] = dict(hbm(2.0 * 3 * E4 * 2 * n4, ms_gate4), tiles=n4)
+        del cur4, old4
+        tiles4 = [torch.randn(g4.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
         canvas4 = torch.empty(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
-        ms_blend = time_calls(torch, lambda: sg.sg_tile_blend(p4, tiles4, canvas4), 10)
-        blend_bytes = 2.0 * (g4.n_tiles * int(np.prod(g4.tile_shape)) + int(np.prod(g4.grid_shape)))
-        kernels["blend_4k"] = {"ms": round(ms_blend, 4), "GB/s": round(blend_bytes / ms_blend * 1e-6, 1),
-                               "frac_hbm_peak": round(blend_bytes / ms_blend * 1e-6 / PEAK_HBM_GBS, 4)}
+        ms_blend = time_calls(torch, lambda: sg.sg_tile_blend(p4, tiles4, canvas4), 20)
+        kernels["blend_4k"] = hbm(2.0 * (n4 * E4 + int(np.prod(g4.grid_shape))), ms_blend)
+        # the 4K canvas step: 20 tile attentions read in place from the canvas tensors + blend
+        q4, k4, v4 = (torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        ms4 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4), 2, warmup=1)
+        kernels["step_4k"] = {"ms": round(ms4, 2), "tiles": n4,
+                              "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4 * 1e-9, 1)}
+        del q4, k4, v4, tiles4, canvas4
         if args.full:
-            q4, k4, v4 = (torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
-            ms4 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4), 2, warmup=1)
-            kernels["step_4k"] = {"ms": round(ms4, 2), "TFLOP/s": round(g4.attention_flops_per_tile * g4.n_tiles / ms4 * 1e-9, 1)}
-            del q4, k4, v4
-        del tiles4, canvas4
+            kernels.update(full_extras(torch, sg, args))
         out["kernels"] = kernels
-        heads = sorted({0, gt.heads - 1, gt.heads // 2})
-        cb, rows, outs = cpu_baseline(torch, gt, x_a[0], 384 if gt.tile_tokens > 10000 else 64, heads)
+        heads = sorted(set(np.linspace(0, gt.heads - 1, min(args.cpu_heads, gt.heads)).round().astype(int).tolist()))
+        cb, rows, outs = cpu_baseline(torch, gt, x_a[0], args.cpu_rows if gt.tile_tokens > 10000 else 64, heads)
         out["cpu_baseline"] = cb
         # the bench's own sanity check: GPU rows of the last attention launch against the oracle sample
         got = cache_out[0].reshape(gt.heads, gt.tile_tokens, gt.head_dim)

@@ -4,7 +4,7 @@
 // contributions of the tiles that cover it, with the separable ramp weights recomputed
 // analytically, and divides by the weight sum.  No accumulator or weight buffers, no atomics:
 // each tile-output element is read once and each canvas element written once, which is the
-// algorithmic HBM traffic.  One thread owns one 16-byte vector of the canvas.
+// algorithmic HBM traffic.  One thread owns one 16-byte vector position of the canvas.
 #include "sg_common.h"
 
 namespace sg {
@@ -29,25 +29,121 @@ __device__ __forceinline__ float ramp(int i, int L, float inv_o1) {
 }
 
 template <int DT>
+__device__ __forceinline__ void fma_vec(const u32x4 val, const float w, float (&acc)[8]) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (DT == SG_BF16) {
+      acc[2 * c] += w * bf16_bits_to_f32(val[c] & 0xffffu);
+      acc[2 * c + 1] += w * __uint_as_float(val[c] & 0xffff0000u);
+    } else {
+      acc[c] += w * __uint_as_float(val[c]);
+    }
+  }
+}
+template <int DT>
+__device__ __forceinline__ u32x4 pack_vec(const float (&acc)[8], const float inv) {
+  u32x4 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (DT == SG_BF16) o[c] = pack_bf16x2(acc[2 * c] * inv, acc[2 * c + 1] * inv);
+    else o[c] = __float_as_uint(acc[c] * inv);
+  }
+  return o;
+}
+
+// A thread owns one 16-byte vector position (y, x, channel group) of the canvas plane and produces it for
+// kPlanes consecutive (head, frame) planes: the covering tiles, their weights and the reciprocal weight sum
+// depend on (y, x) only and are worked out once, and the loads of all planes are in flight together.
+// RC x CC = the largest number of tiles that can cover a token (rows x columns); every candidate has a
+// fixed register slot, absent ones carry weight 0 and are not loaded.
+constexpr int kPlanes = 2;
+
+template <int DT, int RC, int CC>
 __global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void* __restrict__ grid_out) {
   constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
   const uint32_t v = blockIdx.x * kThreads + threadIdx.x;  // vector inside one (head, frame) plane
+  if (v >= a.plane_vecs) return;
+  const uint32_t token = v >> a.vec_per_token_log2;
+  const int cv = v & ((1u << a.vec_per_token_log2) - 1);
+  const int y = token / (uint32_t)a.W, x = token - y * a.W;
+
+  // tiles covering row y: tr*sh <= y < tr*sh + th, i.e. tr in [ceil((y-th+1)/sh), floor(y/sh)]
+  int tr_hi = y / a.sh; if (tr_hi > a.n_rows - 1) tr_hi = a.n_rows - 1;
+  int tr_lo = (y - a.th + a.sh) / a.sh; if (y - a.th + a.sh < 0) tr_lo = 0;
+  int tc_hi = x / a.sw; if (tc_hi > a.n_cols - 1) tc_hi = a.n_cols - 1;
+  int tc_lo = (x - a.tw + a.sw) / a.sw; if (x - a.tw + a.sw < 0) tc_lo = 0;
+
+  const u32x4* src[RC * CC];
+  float w[RC * CC];
+  float wsum = 0.f;
+#pragma unroll
+  for (int ir = 0; ir < RC; ++ir) {
+    const int tr = tr_lo + ir;
+    const int i = y - tr * a.sh;
+    const float wh = (tr <= tr_hi) ? ramp(i, a.th, a.inv_oh1) : 0.f;
+#pragma unroll
+    for (int ic = 0; ic < CC; ++ic) {
+      const int tc = tc_lo + ic;
+      const int j = x - tc * a.sw;
+      const bool on = (tr <= tr_hi) && (tc <= tc_hi);
+      w[ir * CC + ic] = on ? wh * ramp(j, a.tw, a.inv_ow1) : 0.f;
+      wsum += w[ir * CC + ic];
+      src[ir * CC + ic] = on ? (const u32x4*)a.tile[tr * a.n_cols + tc] + ((((int64_t)i * a.tw + j) << a.vec_per_token_log2) + cv)
+                             : nullptr;
+    }
+  }
+  const float inv = 1.0f / wsum;
+  const int64_t tile_plane_vecs = ((int64_t)a.th * a.tw) << a.vec_per_token_log2;
+  const int plane0 = blockIdx.y * kPlanes, n_planes = a.heads * a.T;
+
+  float acc[kPlanes][8];
+#pragma unroll
+  for (int pl = 0; pl < kPlanes; ++pl)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[pl][c] = 0.f;
+#pragma unroll
+  for (int k = 0; k < RC * CC; ++k) {
+    if (w[k] != 0.f) {
+      u32x4 val[kPlanes];
+#pragma unroll
+      for (int pl = 0; pl < kPlanes; ++pl)
+        val[pl] = (plane0 + pl < n_planes) ? __builtin_nontemporal_load(src[k] + (int64_t)(plane0 + pl) * tile_plane_vecs)
+                                           : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int pl = 0; pl < kPlanes; ++pl) fma_vec<DT>(val[pl], w[k], acc[pl]);
+    }
+  }
+#pragma unroll
+  for (int pl = 0; pl < kPlanes; ++pl) {
+    const int plane = plane0 + pl;  // head * T + t
+    if (plane < n_planes) {
+      const int head = plane / a.T, t = plane - head * a.T;
+      const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
+      const int64_t off = (int64_t)head * a.stride_head + n * a.stride_token + (int64_t)cv * kPerVec;
+      u32x4* dst = (u32x4*)((char*)grid_out + off * (DT == SG_BF16 ? 2 : 4));
+      __builtin_nontemporal_store(pack_vec<DT>(acc[pl], inv), dst);
+    }
+  }
+}
+
+// Any coverage: the same computation with loops over the covering tiles, one plane per thread.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void blend_any_kernel(const BlendArgs a, void* __restrict__ grid_out) {
+  constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
+  const uint32_t v = blockIdx.x * kThreads + threadIdx.x;
   if (v >= a.plane_vecs) return;
   const int plane = blockIdx.y;  // head * T + t
   const int head = plane / a.T, t = plane - head * a.T;
   const uint32_t token = v >> a.vec_per_token_log2;
   const int cv = v & ((1u << a.vec_per_token_log2) - 1);
   const int y = token / (uint32_t)a.W, x = token - y * a.W;
-
-  // tiles covering row y: tr*sh <= y < tr*sh + th
   int tr_hi = y / a.sh; if (tr_hi > a.n_rows - 1) tr_hi = a.n_rows - 1;
-  int tr_lo = (y - a.th + a.sh) / a.sh; if (y - a.th + a.sh < 0) tr_lo = 0;   // ceil((y-th+1)/sh)
+  int tr_lo = (y - a.th + a.sh) / a.sh; if (y - a.th + a.sh < 0) tr_lo = 0;
   int tc_hi = x / a.sw; if (tc_hi > a.n_cols - 1) tc_hi = a.n_cols - 1;
   int tc_lo = (x - a.tw + a.sw) / a.sw; if (x - a.tw + a.sw < 0) tc_lo = 0;
-
-  float acc[kPerVec];
+  float acc[8];
 #pragma unroll
-  for (int c = 0; c < kPerVec; ++c) acc[c] = 0.f;
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   float wsum = 0.f;
   for (int tr = tr_lo; tr <= tr_hi; ++tr) {
     const int i = y - tr * a.sh;
@@ -55,32 +151,16 @@ __global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void
     for (int tc = tc_lo; tc <= tc_hi; ++tc) {
       const int j = x - tc * a.sw;
       const float w = wh * ramp(j, a.tw, a.inv_ow1);
-      const int64_t tok = ((int64_t)(plane * a.th + i)) * a.tw + j;       // packed tile token index incl. head
+      const int64_t tok = ((int64_t)(plane * a.th + i)) * a.tw + j;  // packed tile token index incl. head
       const u32x4* src = (const u32x4*)a.tile[tr * a.n_cols + tc] + ((tok << a.vec_per_token_log2) + cv);
-      const u32x4 val = __builtin_nontemporal_load(src);
       wsum += w;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if (DT == SG_BF16) {
-          acc[2 * c] += w * bf16_bits_to_f32(val[c] & 0xffffu);
-          acc[2 * c + 1] += w * __uint_as_float(val[c] & 0xffff0000u);
-        } else {
-          acc[c] += w * __uint_as_float(val[c]);
-        }
-      }
+      fma_vec<DT>(__builtin_nontemporal_load(src), w, acc);
     }
-  }
-  const float inv = 1.0f / wsum;
-  u32x4 o;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (DT == SG_BF16) o[c] = pack_bf16x2(acc[2 * c] * inv, acc[2 * c + 1] * inv);
-    else o[c] = __float_as_uint(acc[c] * inv);
   }
   const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
   const int64_t off = (int64_t)head * a.stride_head + n * a.stride_token + (int64_t)cv * kPerVec;
   u32x4* dst = (u32x4*)((char*)grid_out + off * (DT == SG_BF16 ? 2 : 4));
-  __builtin_nontemporal_store(o, dst);
+  __builtin_nontemporal_store(pack_vec<DT>(acc, 1.0f / wsum), dst);
 }
 
 }  // namespace
@@ -99,9 +179,25 @@ int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_ou
   a.inv_ow1 = 1.0f / (float)(p.tile_w - p.stride_w + 1);
   a.stride_token = p.grid_stride_token; a.stride_head = p.grid_stride_head;
   a.plane_vecs = (uint32_t)((int64_t)p.H * p.W * vpt);
-  dim3 grid((a.plane_vecs + kThreads - 1) / kThreads, p.heads * p.T);
-  if (p.dtype == SG_BF16) blend_kernel<SG_BF16><<<grid, kThreads, 0, s>>>(a, grid_out);
-  else blend_kernel<SG_F32><<<grid, kThreads, 0, s>>>(a, grid_out);
+  const uint32_t gx = (a.plane_vecs + kThreads - 1) / kThreads;
+  const int n_planes = p.heads * p.T;
+  // most tiles that can cover one token, per axis
+  const int rc = (p.tile_h + p.stride_h - 1) / p.stride_h, cc = (p.tile_w + p.stride_w - 1) / p.stride_w;
+  const dim3 grid_pl(gx, (n_planes + kPlanes - 1) / kPlanes), grid_any(gx, n_planes);
+  const bool bf = p.dtype == SG_BF16;
+  if (rc <= 1 && cc <= 1) {
+    if (bf) blend_kernel<SG_BF16, 1, 1><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+    else blend_kernel<SG_F32, 1, 1><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  } else if (rc <= 2 && cc <= 2) {
+    if (bf) blend_kernel<SG_BF16, 2, 2><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+    else blend_kernel<SG_F32, 2, 2><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  } else if (rc <= 3 && cc <= 3) {
+    if (bf) blend_kernel<SG_BF16, 3, 3><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+    else blend_kernel<SG_F32, 3, 3><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  } else {
+    if (bf) blend_any_kernel<SG_BF16><<<grid_any, kThreads, 0, s>>>(a, grid_out);
+    else blend_any_kernel<SG_F32><<<grid_any, kThreads, 0, s>>>(a, grid_out);
+  }
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }

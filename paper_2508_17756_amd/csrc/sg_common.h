@@ -41,10 +41,10 @@ int launch_gate(const void* const* x_cur, const void* const* x_cached, const uin
 int launch_cache_refresh(const void* const* src, void* const* dst, const uint8_t* recompute,
                          uint8_t* has_cache, int n_tiles, int64_t bytes_per_tile, hipStream_t s);
 
-// Gate scratch: per tile kGateBlocks (num, den) fp64 pairs.
-constexpr int kGateBlocks = 128;
+// Gate scratch: per tile kGateSlots (num, den) fp64 pairs, one per workgroup of the partial-sum kernel.
+constexpr int kGateSlots = 1024;
 inline size_t gate_workspace_bytes(int n_tiles) {
-  return (size_t)(n_tiles > 0 ? n_tiles : 1) * kGateBlocks * 2 * sizeof(double);
+  return (size_t)(n_tiles > 0 ? n_tiles : 1) * kGateSlots * 2 * sizeof(double);
 }
 
 // bf16 <-> fp32 on the device.

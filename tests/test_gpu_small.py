@@ -107,12 +107,15 @@ def test_attention_bf16_large_logits_and_constant_v():
 
 # ------------------------------------------------------------------ blend
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", ["tiny2x2", "triple3x2", "placement"])
+@pytest.mark.parametrize("shape", ["tiny2x2", "triple3x2", "placement", "cover5x4", "oddplanes", "single"])
 def test_blend_small(dtype, shape):
     d = 64 if dtype == "f32" else 128
     g = {"tiny2x2": replace(CONFIGS["tiny_f32"], dtype=dtype, head_dim=d),
          "triple3x2": _geom("tr", 2, 9, 7, 5, 4, 2, 3, 3, d, dtype, 51),
-         "placement": _geom("pl", 2, 8, 6, 4, 3, 4, 3, 2, d, dtype, 52)}[shape]
+         "placement": _geom("pl", 2, 8, 6, 4, 3, 4, 3, 2, d, dtype, 52),
+         "cover5x4": _geom("c54", 1, 15, 13, 9, 7, 2, 2, 3, d, dtype, 54),      # up to 5 x 4 tiles per token
+         "oddplanes": _geom("odd", 3, 16, 22, 10, 14, 6, 8, 1, d, dtype, 55),   # 3 (head, frame) planes
+         "single": _geom("one", 3, 5, 9, 5, 9, 5, 9, 3, d, dtype, 56)}[shape]   # one tile = the canvas
     tiles = [randn_tensor(g.tile_shape, dtype, 600 + i).cuda() for i in range(g.n_tiles)]
     out = torch.full(g.grid_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
     sg.sg_tile_blend(sg.make_problem(g), tiles, out)
