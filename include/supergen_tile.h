@@ -2,15 +2,15 @@
  * supergen_tile.h - C ABI of the tile-based denoising hot path on one MI355X (gfx950).
  *
  * The library computes, for a latent canvas of T x H x W tokens that is partitioned into
- * overlapping tiles along H and W only (every tile keeps all T frames; paper Section 4.3,
+ * overlapping tiles along H and W only (every tile keeps all T frames; paper Section 4.2,
  * Algorithm 1 stage 2: PartitionTiles / SliceTile):
  *
  *   sg_tile_attention       3D full self-attention over one tile's tokens (paper Section 2.1
  *                           "full attention"; Section 3: no Q/K/V exchange across tiles)
  *   sg_tile_blend           Fuse: merge all tile outputs into the full canvas (Algorithm 1
- *                           "Fuse"; Section 4.3; Tile Fuser of Section 5)
+ *                           "Fuse"; Section 4.2; Tile Fuser of Section 5)
  *   sg_cache_gate           per-tile cache decision from the relative L1 change of the tile
- *                           input (Equation 3) against a threshold (Equation 8)
+ *                           input (Equation 3) against a threshold (Equation 7)
  *   sg_denoise_step_tiled   one stage-2 step: gate -> attention on the tiles to recompute ->
  *                           cache refresh -> Fuse (Algorithm 1 loop body; Section 5.1 pipeline)
  *
@@ -102,7 +102,7 @@ int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const v
                       int32_t tile_row, int32_t tile_col, void* out_tile, void* stream);
 
 /*
- * Fuse / overlap blend (Algorithm 1 "Fuse"; Section 4.3).  For every canvas token g, head and
+ * Fuse / overlap blend (Algorithm 1 "Fuse"; Section 4.2).  For every canvas token g, head and
  * channel:
  *     out[g] = sum_{tiles covering g} w(g) * O_tile(g)  /  sum_{tiles covering g} w(g)
  *     w = w_h(i) * w_w(j),  w_axis(i) = min(1, (i+1)/(o+1), (L-i)/(o+1)),
@@ -115,7 +115,7 @@ int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const v
 int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_out, void* stream);
 
 /*
- * Cache gate (Equation 3 relative L1 with the cached tensor as denominator; Equation 8:
+ * Cache gate (Equation 3 relative L1 with the cached tensor as denominator; Equation 7:
  * strictly below the threshold reuses, at or above recomputes).  Per tile i:
  *     score[i]     = sum|x_cur[i] - x_cached[i]| / sum|x_cached[i]|      (+inf if the sum is 0)
  *     recompute[i] = !has_cache[i] || score[i] >= threshold

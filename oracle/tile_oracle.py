@@ -5,7 +5,7 @@ fusion, no reordering beyond what each definition states.  Inputs are the stored
 values (bf16 / fp32) widened exactly to fp64 by the caller.
 
 Notation follows the paper: a latent canvas of T x H x W tokens is partitioned
-along H and W only, every tile keeps all T frames (Section 4.3); I_t is a tile's
+along H and W only, every tile keeps all T frames (Section 4.2); I_t is a tile's
 input, O_t its output, tau the cache threshold (Section 5.1).
 
 Geometry arguments are passed as an object `g` with integer attributes
@@ -23,7 +23,7 @@ import numpy as np
 
 
 # --------------------------------------------------------------------------
-# Tile geometry: PartitionTiles / SliceTile (Algorithm 1, stage 2; Section 4.3)
+# Tile geometry: PartitionTiles / SliceTile (Algorithm 1, stage 2; Section 4.2)
 # --------------------------------------------------------------------------
 def tile_origin(g, tile_row, tile_col):
     """Top-left grid token (row, col) of tile (tile_row, tile_col)."""
@@ -92,7 +92,7 @@ def tile_attention(q_grid, k_grid, v_grid, g, tile_row, tile_col, scale,
 
 # --------------------------------------------------------------------------
 # Fuse: merge tile outputs into the full canvas (Algorithm 1 "Fuse";
-# Section 4.3: aggregation before the scheduler update; Tile Fuser, Section 5)
+# Section 4.2: aggregation before the scheduler update; Tile Fuser, Section 5)
 # --------------------------------------------------------------------------
 def ramp_weight(L, o):
     """Per-axis blend weight w(i) = min(1, (i+1)/(o+1), (L-i)/(o+1)), i in [0, L).
@@ -132,7 +132,7 @@ def blend(tile_outs, g):
 
 # --------------------------------------------------------------------------
 # Cache gate: relative L1 change of a tile's input against the cached input
-# (Equation 3: the older tensor is the denominator; Equation 8: strictly below
+# (Equation 3: the older tensor is the denominator; Equation 7: strictly below
 # the threshold reuses, at or above recomputes)
 # --------------------------------------------------------------------------
 def gate_score(x_cur, x_cached):

@@ -1,4 +1,4 @@
-// Fuse / overlap blend of tile outputs into the canvas (paper Algorithm 1 "Fuse", Section 4.3).
+// Fuse / overlap blend of tile outputs into the canvas (paper Algorithm 1 "Fuse", Section 4.2).
 //
 // Gather form of the weighted scatter-accumulate-and-normalise: every canvas element pulls the
 // contributions of the tiles that cover it, with the separable ramp weights recomputed

@@ -1,6 +1,6 @@
 // Cache gate: relative L1 change of each tile's input against its cached input
 // (paper Equation 3, cached tensor in the denominator) compared with the threshold
-// (Equation 8: score >= threshold recomputes).
+// (Equation 7: score >= threshold recomputes).
 //
 // Pure HBM streaming: each input element is read once.  Stage 1 runs one workgroup per compute
 // unit; a thread sums |a-b| and |b| in fp32 over its 16-byte vectors, the workgroup adds its

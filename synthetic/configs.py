@@ -2,7 +2,7 @@
 
 The canvas shapes stand in for the paper's workloads: a 720p tile is a
 160 x 90 latent (80 x 45 tokens after 2 x 2 patchify), 2K is 160 x 90 tokens and
-4K is 240 x 135 tokens, each with 21 latent frames (Section 8.1 of the paper
+4K is 240 x 135 tokens, each with 21 latent frames (Section 8 of the paper, "Workloads"
 gives the tile and canvas sizes); values are i.i.d. N(0, 1).
 """
 from dataclasses import dataclass, replace
