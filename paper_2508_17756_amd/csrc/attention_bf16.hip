@@ -149,7 +149,9 @@ __device__ __forceinline__ float block_max(const f32x16 (&t)[2]) {
 }
 constexpr float kOverflowGuard = 65536.0f;   // a stage's exponentials may grow to 2^16 before the reference moves
 
-template <int D, bool LINEAR>
+enum { kPerLane = 0, kLinear = 1, kScalarWalk = 2 };   // how the loader walks the tile (see the DMA loader)
+
+template <int D, int MODE>
 __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 vw, const float c_log2, const int heads,
                                                                   const int n_qblocks, const int per_xcd,
                                                                   const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
@@ -213,60 +215,126 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 
   // ---- DMA loader: wavefront w moves rows 8w..8w+7 of every stage, 4 rows (1 KiB) per instruction; lane l
   // fills chunk slot (l & 15) of row 8w + 4u + (l >> 4) and therefore fetches the chunk that belongs there.
+  //
+  // kScalarWalk / kLinear: the 8 rows of a wavefront are always consecutive tokens of one tile row (tile
+  // width a multiple of 8, or a packed tile whose rows are adjacent anyway).  The address then splits into
+  // a wave-uniform 64-bit pointer that walks the tile (scalar registers, scalar ALU) and a per-lane byte
+  // offset that never changes, so the steady loop spends no vector instructions on addressing.
+  // kPerLane: every lane walks its own row with a cursor and 32-bit offsets from the head's base.
   const int ld_sub = lane >> 4, ld_slot = lane & 15;
-  RowCursor cur[2];
   uint32_t kchunk[2], vchunk[2];
-  uint32_t koff[2], voff[2];   // byte offsets from kh / vh of the next stage to issue
-  uint32_t last16;
-  {
-    last16 = cursor_at(vw, N - 1).off16;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int row = 8 * wave + 4 * u + ld_sub;
+    kchunk[u] = ld_slot ^ (row & 15);
+    vchunk[u] = ld_slot ^ ((row & 3) << 2);
+  }
+  const uint32_t last16 = cursor_at(vw, N - 1).off16;   // the last valid row: stands in for rows >= N
+  const uint32_t dma_dst = lds0 + wave * (8 * kRowBytes);
+  // scalar walk: pointers to row 8w of the stage to issue (K and V), its tile row / column, lane offsets
+  const char* kcur = (const char*)kh;
+  const char* vcur = (const char*)vh;
+  int32_t row_i = 0, col_j = 0;
+  uint32_t klane[2], vlane[2];
+  // per-lane walk
+  RowCursor cur[2];
+  uint32_t koff[2], voff[2];              // byte offsets from kh / vh of the next stage to issue
+  if (MODE != kPerLane) {
+    const int n0 = 8 * wave;
+    const RowCursor c = cursor_at(vw, n0 < N ? n0 : 0);
+    row_i = __builtin_amdgcn_readfirstlane(c.i);
+    col_j = __builtin_amdgcn_readfirstlane(c.j);
+    const uint64_t first = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)c.off16) << 4;
+    kcur += first;
+    vcur += first;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      klane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + kchunk[u]) << 4;
+      vlane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + vchunk[u]) << 4;
+    }
+  } else {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int row = 8 * wave + 4 * u + ld_sub;
-      kchunk[u] = ld_slot ^ (row & 15);
-      vchunk[u] = ld_slot ^ ((row & 3) << 2);
-      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)row * vw.st16; }
-      else cur[u] = cursor_at(vw, row < N ? row : N - 1);
+      cur[u] = cursor_at(vw, row < N ? row : N - 1);
       koff[u] = (cur[u].off16 + kchunk[u]) << 4;
       voff[u] = (cur[u].off16 + vchunk[u]) << 4;
     }
   }
-  const uint32_t dma_dst = lds0 + wave * (8 * kRowBytes);
+  const uint64_t stage_bytes = (uint64_t)(kBC * 16) * vw.st16;
+  const uint64_t row_skip_bytes = (uint64_t)vw.row_skip16 << 4, frame_skip_bytes = (uint64_t)vw.frame_skip16 << 4;
+  auto scalar_advance = [&]() {   // the wavefront's rows move kBC tokens on
+    uint64_t delta = stage_bytes;
+    if (MODE == kScalarWalk) {
+      col_j += kBC;
+      if (vw.tw >= kBC) {         // at most one tile-row wrap: branch-free
+        const bool wrap = col_j >= vw.tw;
+        col_j -= wrap ? vw.tw : 0;
+        row_i += wrap ? 1 : 0;
+        const bool fwrap = row_i == vw.th;
+        row_i = fwrap ? 0 : row_i;
+        delta += (wrap ? row_skip_bytes : 0) + (fwrap ? frame_skip_bytes : 0);
+      } else {
+        while (col_j >= vw.tw) {
+          col_j -= vw.tw;
+          delta += row_skip_bytes;
+          if (++row_i == vw.th) { row_i = 0; delta += frame_skip_bytes; }
+        }
+      }
+    }
+    kcur += delta;
+    vcur += delta;
+  };
   // issue stage `blk` (all of its rows below N) into ring slot `st`; advance to the next stage
   auto issue_full = [&](int blk, int st) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      dma16(kh, koff[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
-      dma16(vh, voff[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-      if (LINEAR) {
-        koff[u] += (kBC * 16) * vw.st16;
-        voff[u] += (kBC * 16) * vw.st16;
+      if (MODE != kPerLane) {
+        dma16(kcur, klane[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+        dma16(vcur, vlane[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
       } else {
+        dma16(kh, koff[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+        dma16(vh, voff[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
         const int n = blk * kBC + 8 * wave + 4 * u + ld_sub;
         if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
         koff[u] = (cur[u].off16 + kchunk[u]) << 4;
         voff[u] = (cur[u].off16 + vchunk[u]) << 4;
       }
     }
+    if (MODE != kPerLane) scalar_advance();
   };
   // same for a stage that may hold rows >= N: those lanes fetch the last valid row (masked later)
   auto issue_any = [&](int blk, int st) {
+    const int n0 = blk * kBC + 8 * wave;   // wave-uniform
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const int n = blk * kBC + 8 * wave + 4 * u + ld_sub;
-      const uint32_t ko = (n < N) ? koff[u] : ((last16 + kchunk[u]) << 4);
-      const uint32_t vo = (n < N) ? voff[u] : ((last16 + vchunk[u]) << 4);
-      dma16(kh, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
-      dma16(vh, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-      if (LINEAR) {
-        koff[u] += (kBC * 16) * vw.st16;
-        voff[u] += (kBC * 16) * vw.st16;
+      const int n = n0 + 4 * u + ld_sub;
+      if (MODE != kPerLane) {
+        if (n0 + 7 < N) {          // all 8 rows valid
+          dma16(kcur, klane[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+          dma16(vcur, vlane[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+        } else if (n0 < N) {       // partly valid: rows >= N take the last row, which lies at or after row n0
+          const uint32_t back = (uint32_t)(((const char*)kh + ((uint64_t)last16 << 4)) - kcur);
+          const uint32_t ko = (n < N) ? klane[u] : back + (kchunk[u] << 4);
+          const uint32_t vo = (n < N) ? vlane[u] : back + (vchunk[u] << 4);
+          dma16(kcur, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+          dma16(vcur, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+        } else {                   // no valid row: every lane takes the last row
+          const uint64_t lastb = (uint64_t)last16 << 4;
+          dma16((const char*)kh + lastb, kchunk[u] << 4, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+          dma16((const char*)vh + lastb, vchunk[u] << 4, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+        }
       } else {
+        const uint32_t ko = (n < N) ? koff[u] : ((last16 + kchunk[u]) << 4);
+        const uint32_t vo = (n < N) ? voff[u] : ((last16 + vchunk[u]) << 4);
+        dma16(kh, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+        dma16(vh, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
         if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
         koff[u] = (cur[u].off16 + kchunk[u]) << 4;
         voff[u] = (cur[u].off16 + vchunk[u]) << 4;
       }
     }
+    if (MODE != kPerLane && n0 + kBC < N) scalar_advance();
   };
 
   f32x16 oacc[D / 32];
@@ -290,13 +358,19 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, both);
   };
-  // S^T = K Q^T of the stage at LDS byte offset `off`: two independent accumulator chains, fragment reads
-  // issued two steps ahead of the MFMAs that consume them
+  // Fragment reads run kPF MFMA steps ahead of their use; the first K fragments of a QK product are read
+  // during the last steps of the PV product before it, so the matrix pipe does not drain between the two.
+  // (Reading the first V^T fragments ahead, during the softmax, was measured 7 % slower and is not done.)
   constexpr int kPF = 2;
-  auto qk = [&](int off, f32x16 (&s)[2]) {
+  bf16x8 kpre[kPF][2];    // K fragments of the first kPF QK steps, read during the PV tail
+  // S^T = K Q^T of the stage at LDS byte offset `off`: two independent accumulator chains
+  auto qk = [&](int off, f32x16 (&s)[2], bool prefetched) {
     bf16x8 a[D / 16][2];
 #pragma unroll
-    for (int kk = 0; kk < kPF; ++kk) { a[kk][0] = kfrag(kk, 0, off); a[kk][1] = kfrag(kk, 1, off); }
+    for (int kk = 0; kk < kPF; ++kk) {
+      if (prefetched) { a[kk][0] = kpre[kk][0]; a[kk][1] = kpre[kk][1]; }
+      else { a[kk][0] = kfrag(kk, 0, off); a[kk][1] = kfrag(kk, 1, off); }
+    }
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) {
       if (kk + kPF < D / 16) { a[kk + kPF][0] = kfrag(kk + kPF, 0, off); a[kk + kPF][1] = kfrag(kk + kPF, 1, off); }
@@ -311,8 +385,9 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d)
-  auto pv = [&](int off, const bf16x8 (&pp)[4]) {
+  // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d); if a QK product follows
+  // (K stage at `k_off`), its first fragments are read in the last steps
+  auto pv = [&](int off, const bf16x8 (&pp)[4], int k_off, bool k_follows) {
     bf16x8 a[16];
 #pragma unroll
     for (int i = 0; i < 2 * kPF; ++i) a[i] = vfrag(i >> 2, i & 3, off);
@@ -321,6 +396,10 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
       if (i + 2 * kPF < 16) {
         a[i + 2 * kPF] = vfrag((i + 2 * kPF) >> 2, (i + 2 * kPF) & 3, off);
         a[i + 2 * kPF + 1] = vfrag((i + 2 * kPF + 1) >> 2, (i + 2 * kPF + 1) & 3, off);
+      } else if (k_follows) {
+        const int kk = (i + 2 * kPF - 16) / 2;
+        kpre[kk][0] = kfrag(kk, 0, k_off);
+        kpre[kk][1] = kfrag(kk, 1, k_off);
       }
       __builtin_amdgcn_sched_barrier(0);
       oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], pp[i >> 2], oacc[i & 3], 0, 0, 0);
@@ -380,8 +459,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     constexpr int ST = decltype(st_tag)::value;
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
-    pv(ST * kTileBytes, p);
-    qk(((ST + 1) % kStages) * kTileBytes, s);
+    pv(ST * kTileBytes, p, ((ST + 1) % kStages) * kTileBytes, true);
+    qk(((ST + 1) % kStages) * kTileBytes, s, true);
     asm volatile("" : : "v"(s[0]), "v"(s[1]));
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
@@ -389,8 +468,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   auto mfma_phase_any = [&](int k) {
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
-    pv((k % kStages) * kTileBytes, p);
-    if (k + 1 < n_blocks) qk(((k + 1) % kStages) * kTileBytes, s);
+    pv((k % kStages) * kTileBytes, p, ((k + 1) % kStages) * kTileBytes, k + 1 < n_blocks);
+    if (k + 1 < n_blocks) qk(((k + 1) % kStages) * kTileBytes, s, true);
     asm volatile("" : : "v"(s[0]), "v"(s[1]));
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
@@ -405,7 +484,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     if (b < n_blocks) issue_any(b, b);
   wait_stage(n_blocks >= 3 ? 2 : (n_blocks == 2 ? 1 : 0));
   meet();
-  qk(0, s);
+  qk(0, s, false);
   asm volatile("" : : "v"(s[0]), "v"(s[1]));
   const int n_steady = (n_blocks >= 2 * kStages) ? kStages + ((n_blocks - 2 * kStages) / kStages) * kStages : 0;
 
@@ -493,10 +572,6 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
                           const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
   if (head_dim != 128) return SG_ERR_UNSUPPORTED;
-  // The streaming loads address a head's K/V with 32-bit byte offsets from a wave-uniform base; canvases
-  // whose per-head extent does not fit take the kernel with 64-bit addressing.
-  const int64_t head_extent = ((int64_t)tv.T * tv.H * tv.W) * tv.stride_token + tv.base;
-  if (head_extent * 2 >= (1ll << 32)) return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
   View16 vw;
   vw.base16 = (uint32_t)(tv.base / 8);
   vw.st16 = (uint32_t)(tv.stride_token / 8);
@@ -504,24 +579,35 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   vw.frame_skip16 = (uint32_t)((int64_t)(tv.H - tv.th) * tv.W) * vw.st16;
   vw.th = tv.th; vw.tw = tv.tw; vw.N = tv.N;
   vw.head16 = (uint32_t)(tv.stride_head / 8);
+  // a wavefront moves 8 consecutive tile tokens per stage: contiguous in memory whenever they cannot
+  // straddle a tile row (tile width a multiple of 8) or the tile rows are themselves adjacent (packed tile)
   const bool linear = (tv.W == tv.tw && tv.H == tv.th);
+  const int mode = linear ? kLinear : (tv.tw % 8 == 0 ? kScalarWalk : kPerLane);
+  // The per-lane cursors address a head's K/V with 32-bit byte offsets from a wave-uniform base; canvases
+  // whose per-head extent does not fit take the kernel with 64-bit addressing.
+  const int64_t head_extent = ((int64_t)tv.T * tv.H * tv.W) * tv.stride_token + tv.base;
+  if (mode == kPerLane && head_extent * 2 >= (1ll << 32))
+    return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
   const int n_qblocks = (tv.N + kBR - 1) / kBR;
   const int total = n_qblocks * heads;
   const int per_xcd = (total + kXcd - 1) / kXcd;
   const float c_log2 = scale * 1.4426950408889634f;
   dim3 grid(per_xcd * kXcd);
-  static bool attr_set[2] = {false, false};
-  if (linear) {
-    auto kern = attention_bf16_kernel<128, true>;
-    if (!attr_set[0]) { SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)); attr_set[0] = true; }
+  static bool attr_set[3] = {false, false, false};
+  auto launch = [&](auto kern, int slot) -> int {
+    if (!attr_set[slot]) {
+      SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+      attr_set[slot] = true;
+    }
     kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
                                            (const u32x4*)v, (uint16_t*)out, run_flag);
-  } else {
-    auto kern = attention_bf16_kernel<128, false>;
-    if (!attr_set[1]) { SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes)); attr_set[1] = true; }
-    kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                           (const u32x4*)v, (uint16_t*)out, run_flag);
-  }
+    return SG_OK;
+  };
+  int st = SG_OK;
+  if (mode == kLinear) st = launch(attention_bf16_kernel<128, kLinear>, kLinear);
+  else if (mode == kScalarWalk) st = launch(attention_bf16_kernel<128, kScalarWalk>, kScalarWalk);
+  else st = launch(attention_bf16_kernel<128, kPerLane>, kPerLane);
+  if (st != SG_OK) return st;
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }

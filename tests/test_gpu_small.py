@@ -47,7 +47,9 @@ BF16_CASES = [
     ("packed_n273", 3, 7, 13, 7, 13, 7, 13, 3),         # key tail 17 < 32: second half block all masked
     ("packed_n40", 1, 5, 8, 5, 8, 5, 8, 1),             # fewer keys than one block
     ("view_2x2", 3, 16, 22, 10, 14, 6, 8, 2),           # overlapping tiles read in place, N = 420
-    ("view_3x3", 2, 20, 40, 12, 24, 4, 8, 2),           # N = 576, triple row coverage
+    ("view_3x3", 2, 20, 40, 12, 24, 4, 8, 2),           # N = 576, triple row coverage; tile width 24: scalar walk, several row wraps per stage
+    ("view_w72", 2, 8, 136, 6, 72, 2, 64, 2),           # N = 864, tile width 72 >= one stage: scalar walk, at most one wrap per stage
+    ("view_w8", 3, 40, 12, 32, 8, 8, 4, 1),             # N = 768, tile width 8: eight row wraps per stage, frame wraps
 ]
 
 
@@ -72,10 +74,12 @@ def test_attention_bf16_token_major_layout():
     assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv_hm, 1, 1), "bf16")
 
 
-def test_attention_bf16_wide_token_stride_takes_general_addressing():
-    """A canvas whose per-head extent exceeds 4 GiB (token stride of 2^20 elements) is served by the
-    kernel with 64-bit addressing; same numbers as the oracle."""
-    g = _geom("wide", 2, 32, 40, 16, 20, 16, 20, 1, 128, "bf16", 71)        # 2560 canvas tokens, N = 640
+@pytest.mark.parametrize("tw", [20, 24], ids=["per_lane_rows", "scalar_walk"])
+def test_attention_bf16_wide_token_stride_takes_general_addressing(tw):
+    """A canvas whose per-head extent exceeds 4 GiB (token stride of 2^20 elements): a tile width that is
+    not a multiple of 8 goes to the kernel with 64-bit per-lane addressing, a multiple of 8 stays on the
+    streaming kernel, whose scalar walk is 64-bit; same numbers as the oracle either way."""
+    g = _geom("wide", 2, 32, 2 * tw, 16, tw, 16, tw, 1, 128, "bf16", 71)      # N = 640 / 768
     stride = 1 << 20
     dense = canvas_qkv(g)
     wide = []
