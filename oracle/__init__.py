@@ -18,4 +18,11 @@ from .tile_oracle import (  # noqa: F401
     cache_gate,
     StepState,
     denoise_step_tiled,
+    rel_l1,
+    accumulated_error,
+    gain,
+    GainState,
+    gain_gate,
+    gain_refresh,
+    denoise_step_gain,
 )

@@ -17,7 +17,11 @@ Pins (tests/test_oracle_*.py): agreement with torch's fp64
 scaled_dot_product_attention, a separately written triple-loop brute force,
 closed forms (two-key softmax, scale 0 -> mean(V), two-tile ramp weights sum to
 1, |a| scaling of the relative L1), invariances (row sums, permutation, key
-shift) and the tile counts the paper states for 2K and 4K canvases.
+shift) and the tile counts the paper states for 2K and 4K canvases; for the
+gain / path-length policy (tests/test_oracle_gain.py): geometric drift with a
+closed-form recompute period, g = 1 for any scalar model, g_c L = Equation 4's
+accumulated error whenever the gain is constant, exact reuse for a model that
+adds a constant, and a hand-computed three-step trace.
 """
 import numpy as np
 
@@ -205,3 +209,133 @@ def denoise_step_tiled(tile_x, g, scale, state, threshold, attend=None):
             state.has_cache[i] = True
     canvas = blend(state.cache_out, g)
     return canvas, scores, recompute
+
+
+# --------------------------------------------------------------------------
+# Inter-step tile-wise cache policy of Section 5.1: cache residual
+# delta_c = O_c - I_c, gain g_c (Equation 5), latent path length L_{c->t}
+# (Equation 6) and the recompute rule g_c L_{c->t} >= tau (Equation 7).
+#
+# The paper writes ||.|| without naming the norm; its profiling figures and
+# Equation 3 use the relative L1 distance, and its thresholds (0.05, 0.09) are
+# dimensionless, so every ||X_z - X_{z-1}|| below is the relative L1 change
+# ||X_z - X_{z-1}||_1 / ||X_{z-1}||_1 (older tensor in the denominator).
+# --------------------------------------------------------------------------
+def rel_l1(new, old):
+    """||new - old||_1 / ||old||_1 ; +inf when the denominator is 0."""
+    return gate_score(new, old)
+
+
+def accumulated_error(outputs):
+    """Equation 4: E_{c->t} = sum_{z=c+1..t} ||O_z - O_{z-1}|| for outputs [O_c, ..., O_t]."""
+    return float(sum(rel_l1(outputs[z], outputs[z - 1]) for z in range(1, len(outputs))))
+
+
+def gain(o_new, o_old, i_new, i_old):
+    """Equation 5: g_t = ||O_t - O_{t-1}|| / ||I_t - I_{t-1}||."""
+    return rel_l1(o_new, o_old) / rel_l1(i_new, i_old)
+
+
+class GainState:
+    """Tile-wise Cache Store of Section 5.1, per tile:
+    x_prev, o_prev   I_{t-1} and O_{t-1} (has_prev says whether a previous step exists)
+    delta            cache residual delta_c = O_c - I_c of the last recomputed step c
+    gain, has_gain   g_c and whether it is known yet (it needs two consecutive outputs)
+    path_len         L_{c->t}, the latent path length since step c
+    """
+
+    def __init__(self, n_tiles):
+        self.has_prev = [False] * n_tiles
+        self.has_gain = [False] * n_tiles
+        self.gain = [0.0] * n_tiles
+        self.path_len = [0.0] * n_tiles
+        self.x_prev = [None] * n_tiles
+        self.o_prev = [None] * n_tiles
+        self.delta = [None] * n_tiles
+
+
+def gain_gate(x_cur, state, thresholds):
+    """Error Calculator + Threshold Comparator: per tile
+        d_t = ||I_t - I_{t-1}||          (0 on the first step: nothing to compare with)
+        L  <- L + d_t                    (Equation 6)
+        score = g_c * L                  (+inf while g_c is unknown)
+        reuse iff g_c known and score < tau_i, else recompute   (Equation 7)
+    x_cur[i] is tile i's flattened input.  Updates state.path_len.
+    Returns (step_change d, scores, recompute)."""
+    n = len(x_cur)
+    d = np.zeros(n)
+    scores = np.full(n, np.inf)
+    recompute = np.ones(n, dtype=bool)
+    for i in range(n):
+        if state.has_prev[i]:
+            d[i] = rel_l1(x_cur[i], state.x_prev[i])
+        state.path_len[i] += d[i]
+        if state.has_gain[i]:
+            scores[i] = state.gain[i] * state.path_len[i]
+            recompute[i] = not (scores[i] < float(thresholds[i]))
+    return d, scores, recompute
+
+
+def gain_refresh(o_new, latent, recompute, d, state):
+    """After the Denoising Engine ran on the tiles to recompute (o_new[i] holds their
+    new outputs, anything for the others).  Per tile:
+      recomputed: g_c <- ||O_t - O_{t-1}|| / d_t if a previous output exists and d_t is
+                  finite and > 0 (otherwise g_c keeps its state); L <- 0;
+                  delta_c <- O_t - I_t                              (c <- t)
+      reused:     O_t <- I_t + delta_c                              (Residual Approximation)
+    latent[i] is the tensor I_t the residual is taken against (same shape as O).
+    Returns the list of this step's outputs O_t; the caller stores them (and the
+    inputs) as the next step's o_prev / x_prev."""
+    outs = []
+    for i in range(len(o_new)):
+        lat = np.asarray(latent[i], dtype=np.float64)
+        if recompute[i]:
+            o = np.asarray(o_new[i], dtype=np.float64)
+            if state.has_prev[i] and np.isfinite(d[i]) and d[i] > 0.0:
+                state.gain[i] = rel_l1(o, state.o_prev[i]) / d[i]
+                state.has_gain[i] = True
+            state.path_len[i] = 0.0
+            state.delta[i] = o - lat
+        else:
+            o = lat + state.delta[i]
+        outs.append(o)
+    return outs
+
+
+def denoise_step_gain(tile_x, g, scale, state, thresholds, model=None, latent_of=None, store=None):
+    """One stage-2 step under the cache policy of Section 5.1.
+
+    tile_x[i] = (Q, K, V) packed tiles.  The gate reads concat(Q, K, V) as the tile
+    input I_t; the residual is taken against latent_of(tile_x[i]) (default: Q, which
+    has the shape of the output).  `model(i, Q, K, V)` is the Denoising Engine
+    (default: full attention per head).  `store(a)` rounds an output to the storage
+    type before it enters the state (default: identity).
+    Returns (canvas, step_change, scores, recompute, outs)."""
+    n = len(tile_x)
+    flat = [np.concatenate([np.asarray(t, dtype=np.float64).ravel() for t in x]) for x in tile_x]
+    latent = [np.asarray((latent_of(x) if latent_of else x[0]), dtype=np.float64) for x in tile_x]
+    d, scores, recompute = gain_gate(flat, state, thresholds)
+    o_new = [None] * n
+    for i in range(n):
+        if recompute[i]:
+            Q, K, V = (np.asarray(t, dtype=np.float64) for t in tile_x[i])
+            if model is not None:
+                o_new[i] = model(i, Q, K, V)
+            else:
+                heads, dd = Q.shape[0], Q.shape[-1]
+                o = np.stack([attention(Q[a].reshape(-1, dd), K[a].reshape(-1, dd), V[a].reshape(-1, dd), scale)
+                              for a in range(heads)])
+                o_new[i] = o.reshape(Q.shape)
+            if store is not None:
+                o_new[i] = store(o_new[i])
+        else:
+            o_new[i] = latent[i]   # placeholder, not read
+    outs = gain_refresh(o_new, latent, recompute, d, state)
+    if store is not None:
+        outs = [store(o) for o in outs]
+    for i in range(n):
+        state.x_prev[i] = flat[i]
+        state.o_prev[i] = outs[i]
+        state.has_prev[i] = True
+    canvas = blend(outs, g)
+    return canvas, d, scores, recompute, outs
