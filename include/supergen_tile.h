@@ -165,6 +165,80 @@ typedef struct sg_step_io {
  */
 int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Inter-step tile-wise cache policy of the paper (Section 5.1).  Where sg_cache_gate compares the
+ * tile input with the cached input directly, this policy keeps per tile
+ *     delta_c   the cache residual O_c - I_c of the last recomputed step c (fp32, device buffer),
+ *     g_c       the gain ||O_t - O_{t-1}|| / ||I_t - I_{t-1}|| measured when step c ran (Equation 5),
+ *     L         the latent path length sum ||I_z - I_{z-1}|| since step c (Equation 6),
+ * reuses a tile while g_c * L < tau_i with O_t = I_t + delta_c (Residual Approximation), and
+ * otherwise recomputes it and sets c = t (Equation 7).  The paper does not name the norm; every
+ * ||X_z - X_{z-1}|| here is the relative L1 change sum|X_z - X_{z-1}| / sum|X_{z-1}| of Equation 3
+ * (+inf if the denominator is 0), which makes the thresholds dimensionless like the paper's.
+ * While g_c is unknown (it needs two consecutive outputs) the tile recomputes: a tile's first two
+ * steps always run the engine.  On reused steps O_{t-1} is the approximated output.
+ * The caller double-buffers inputs and outputs: this step's x_cur / out_cur are the next step's
+ * x_prev / out_prev. */
+typedef struct sg_gain_state {   /* device arrays of n_tiles entries, read and updated by the calls below */
+  uint8_t* has_prev;   /* 1 once the tile has a previous step (x_prev / out_prev valid); start at 0 */
+  uint8_t* has_gain;   /* 1 once g_c is known; start at 0                                           */
+  float* gain;         /* g_c                                                                       */
+  float* path_len;     /* L; start at 0                                                             */
+} sg_gain_state;
+
+/*
+ * Error Calculator and Threshold Comparator (Equations 6 and 7).  Per tile i:
+ *     d = has_prev ? ||x_cur - x_prev|| : 0;   L += d;   score = has_gain ? g_c * L : +inf;
+ *     recompute = !(has_gain && score < tau_i)         (a NaN score recomputes)
+ *   x_cur, x_prev    host arrays of n_tiles device pointers, elems_per_tile elements each (as sg_cache_gate)
+ *   threshold        tau for every tile, unless tile_thresholds (device, n_tiles floats) is not NULL
+ *   step_change      device, n_tiles floats (out): d, consumed by sg_gain_refresh
+ *   scores, recompute, workspace: as sg_cache_gate
+ */
+int sg_gain_gate(const void* const* x_cur, const void* const* x_prev, const sg_gain_state* state,
+                 int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float threshold,
+                 const float* tile_thresholds, float* step_change, float* scores, uint8_t* recompute,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cache Store update after the engine has written out_cur[i] for the tiles to recompute.  Per tile:
+ *   recomputed: delta[i] = out_cur[i] - latent[i]; if has_prev and 0 < d < inf:
+ *               g_c = ||out_cur - out_prev|| / d, has_gain = 1 (else g_c keeps its state); L = 0;
+ *   reused:     out_cur[i] = latent[i] + delta[i]   (one rounding to the tensors' type);
+ *   every tile: has_prev = 1.
+ *   out_cur, out_prev, latent  host arrays of device pointers, elems_per_tile elements of `dtype`
+ *                              (latent[i] = the tensor I_t the residual is taken against)
+ *   delta                      host array of device pointers, elems_per_tile floats each
+ *   elems_per_tile             a multiple of 8
+ */
+int sg_gain_refresh(void* const* out_cur, const void* const* out_prev, const void* const* latent,
+                    float* const* delta, const uint8_t* recompute, const float* step_change,
+                    const sg_gain_state* state, int32_t n_tiles, int64_t elems_per_tile, int32_t dtype,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Buffers of one step under this policy; arrays of pointers are host arrays of device pointers. */
+typedef struct sg_gain_step_io {
+  const void* const* tile_x;   /* this step's packed tile inputs [3][heads][T][tile_h][tile_w][d] (Q, K, V) */
+  const void* const* prev_x;   /* the previous step's (not read while has_prev = 0)                          */
+  const void* const* latent;   /* I_t per tile, packed tile shape; NULL: the Q part of tile_x                */
+  void* const* out_cur;        /* this step's tile outputs (written for every tile; the blend reads these)   */
+  const void* const* out_prev; /* the previous step's                                                        */
+  float* const* delta;         /* cache residuals                                                            */
+  sg_gain_state state;
+  float threshold;
+  const float* tile_thresholds; /* device or NULL */
+  float* step_change;           /* device, n_tiles (out) */
+  float* scores;                /* device, n_tiles (out) */
+  uint8_t* recompute;           /* device, n_tiles (out) */
+  void* grid_out;
+  void* workspace;
+  size_t workspace_bytes;
+} sg_gain_step_io;
+
+/* One stage-2 step: sg_gain_gate on the packed inputs -> attention of the tiles to recompute into
+ * out_cur -> sg_gain_refresh -> Fuse of out_cur into grid_out.  Nothing is read back. */
+int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,6 +44,24 @@ class sg_step_io(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
+class sg_gain_state(ctypes.Structure):
+    _fields_ = [("has_prev", ctypes.c_void_p), ("has_gain", ctypes.c_void_p),
+                ("gain", ctypes.c_void_p), ("path_len", ctypes.c_void_p)]
+
+
+class sg_gain_step_io(ctypes.Structure):
+    _fields_ = [("tile_x", ctypes.POINTER(ctypes.c_void_p)), ("prev_x", ctypes.POINTER(ctypes.c_void_p)),
+                ("latent", ctypes.POINTER(ctypes.c_void_p)),
+                ("out_cur", ctypes.POINTER(ctypes.c_void_p)), ("out_prev", ctypes.POINTER(ctypes.c_void_p)),
+                ("delta", ctypes.POINTER(ctypes.c_void_p)),
+                ("state", sg_gain_state),
+                ("threshold", ctypes.c_float),
+                ("tile_thresholds", ctypes.c_void_p),
+                ("step_change", ctypes.c_void_p), ("scores", ctypes.c_void_p), ("recompute", ctypes.c_void_p),
+                ("grid_out", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
 def library_path():
     return os.path.join(_PKG, "libsupergen_tile.so")
 
@@ -78,6 +96,14 @@ def load_library():
     lib.sg_cache_gate.argtypes = [pp, pp, vp, i32, i64, i32, f32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sg_denoise_step_tiled.restype = ctypes.c_int
     lib.sg_denoise_step_tiled.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_step_io), vp]
+    lib.sg_gain_gate.restype = ctypes.c_int
+    lib.sg_gain_gate.argtypes = [pp, pp, ctypes.POINTER(sg_gain_state), i32, i64, i32, f32, vp, vp, vp, vp, vp,
+                                 ctypes.c_size_t, vp]
+    lib.sg_gain_refresh.restype = ctypes.c_int
+    lib.sg_gain_refresh.argtypes = [pp, pp, pp, pp, vp, vp, ctypes.POINTER(sg_gain_state), i32, i64, i32, vp,
+                                    ctypes.c_size_t, vp]
+    lib.sg_denoise_step_gain.restype = ctypes.c_int
+    lib.sg_denoise_step_gain.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_gain_step_io), vp]
     _LIB = lib
     return lib
 
@@ -196,4 +222,70 @@ def sg_denoise_step_tiled(p, grid_out, cache_out, q=None, k=None, v=None, tile_x
     io.workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = load_library().sg_denoise_step_tiled(ctypes.byref(p), ctypes.byref(io), _stream())
     _check(st, "sg_denoise_step_tiled")
+    return grid_out
+
+
+class GainState:
+    """Device-resident per-tile state of the gain / path-length cache policy (zero-initialised)."""
+
+    def __init__(self, n_tiles, device="cuda"):
+        import torch
+        n = max(1, int(n_tiles))
+        self.has_prev = torch.zeros(n, dtype=torch.uint8, device=device)
+        self.has_gain = torch.zeros(n, dtype=torch.uint8, device=device)
+        self.gain = torch.zeros(n, dtype=torch.float32, device=device)
+        self.path_len = torch.zeros(n, dtype=torch.float32, device=device)
+
+    def as_struct(self):
+        st = sg_gain_state()
+        st.has_prev, st.has_gain = _ptr(self.has_prev), _ptr(self.has_gain)
+        st.gain, st.path_len = _ptr(self.gain), _ptr(self.path_len)
+        return st
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+def sg_gain_gate(x_cur, x_prev, state, threshold, step_change, scores, recompute, workspace,
+                 tile_thresholds=None, elems_per_tile=None):
+    n = len(x_cur)
+    elems = int(elems_per_tile if elems_per_tile is not None else (x_cur[0].numel() if n else 0))
+    dt = _dtype_code(x_cur[0]) if n else SG_BF16
+    st = state.as_struct()
+    rc = load_library().sg_gain_gate(_ptr_array(x_cur), _ptr_array(x_prev), ctypes.byref(st), n, elems, dt,
+                                     float(threshold), _ptr(tile_thresholds), _ptr(step_change), _ptr(scores),
+                                     _ptr(recompute), _ptr(workspace), _nbytes(workspace), _stream())
+    _check(rc, "sg_gain_gate")
+    return step_change, scores, recompute
+
+
+def sg_gain_refresh(out_cur, out_prev, latent, delta, recompute, step_change, state, workspace, elems_per_tile=None):
+    n = len(out_cur)
+    elems = int(elems_per_tile if elems_per_tile is not None else (out_cur[0].numel() if n else 0))
+    dt = _dtype_code(out_cur[0]) if n else SG_BF16
+    st = state.as_struct()
+    rc = load_library().sg_gain_refresh(_ptr_array(out_cur), _ptr_array(out_prev), _ptr_array(latent), _ptr_array(delta),
+                                        _ptr(recompute), _ptr(step_change), ctypes.byref(st), n, elems, dt,
+                                        _ptr(workspace), _nbytes(workspace), _stream())
+    _check(rc, "sg_gain_refresh")
+    return out_cur
+
+
+def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, state, threshold, step_change,
+                         scores, recompute, workspace, latent=None, tile_thresholds=None):
+    io = sg_gain_step_io()
+    keep = [_ptr_array(tile_x), _ptr_array(prev_x), _ptr_array(out_cur), _ptr_array(out_prev), _ptr_array(delta)]
+    io.tile_x, io.prev_x, io.out_cur, io.out_prev, io.delta = keep
+    if latent is not None:
+        keep.append(_ptr_array(latent))
+        io.latent = keep[-1]
+    io.state = state.as_struct()
+    io.threshold = float(threshold)
+    io.tile_thresholds = _ptr(tile_thresholds)
+    io.step_change, io.scores, io.recompute = _ptr(step_change), _ptr(scores), _ptr(recompute)
+    io.grid_out = _ptr(grid_out)
+    io.workspace, io.workspace_bytes = _ptr(workspace), _nbytes(workspace)
+    rc = load_library().sg_denoise_step_gain(ctypes.byref(p), ctypes.byref(io), _stream())
+    _check(rc, "sg_denoise_step_gain")
     return grid_out

@@ -54,6 +54,7 @@ __global__ __launch_bounds__(kThreads) void gate_partial_kernel(GatePtrs ptrs, c
   const int64_t v0 = (int64_t)blk * per_blk;
   const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
   __shared__ double s_num[2][kThreads / 64], s_den[2][kThreads / 64];
+  int par = 0;   // LDS slot of the next workgroup reduction; alternates, so one barrier per reduction suffices
   for (int tile = 0; tile < n_tiles; ++tile) {
     double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk) * 2;
     if (!has_cache[tile0 + tile]) {  // no cached input: nothing to compare, buffers are not read
@@ -92,13 +93,11 @@ __global__ __launch_bounds__(kThreads) void gate_partial_kernel(GatePtrs ptrs, c
       }
     }
     // fixed-order tree over the workgroup: wavefront shuffles, then one value per wavefront via LDS
-    // (two LDS slots alternate between tiles, so one barrier per tile suffices)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
       num += __shfl_down(num, off, 64);
       den += __shfl_down(den, off, 64);
     }
-    const int par = tile & 1;
     if ((threadIdx.x & 63) == 0) { s_num[par][threadIdx.x >> 6] = num; s_den[par][threadIdx.x >> 6] = den; }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -107,6 +106,7 @@ __global__ __launch_bounds__(kThreads) void gate_partial_kernel(GatePtrs ptrs, c
       out[0] = n;
       out[1] = d;
     }
+    par ^= 1;
   }
 }
 
@@ -161,30 +161,268 @@ __global__ __launch_bounds__(kThreads) void cache_refresh_kernel(RefreshPtrs ptr
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Inter-step tile-wise cache policy (paper Section 5.1): cache residual delta_c = O_c - I_c, gain g_c
+// (Equation 5), latent path length L_{c->t} (Equation 6), rule g_c L >= tau recomputes (Equation 7).
+// Every ||X_z - X_{z-1}|| is the relative L1 change with the older tensor as denominator (Equation 3's
+// distance), computed by the two-stage reduction above.
+
+// Error Calculator + Threshold Comparator, one workgroup per tile.
+__global__ __launch_bounds__(kFinalThreads) void gain_gate_finalize_kernel(
+    const double* __restrict__ partial, int n_slots, const uint8_t* __restrict__ has_prev,
+    const uint8_t* __restrict__ has_gain, const float* __restrict__ gain, float* __restrict__ path_len, float threshold,
+    const float* __restrict__ tile_thresholds, float* __restrict__ step_change, float* __restrict__ scores,
+    uint8_t* __restrict__ recompute) {
+  const int tile = blockIdx.x;
+  __shared__ double s_num[kFinalThreads], s_den[kFinalThreads];
+  double n = 0.0, d = 0.0;
+  for (int sl = threadIdx.x; sl < n_slots; sl += kFinalThreads) {
+    n += partial[((size_t)tile * kGateSlots + sl) * 2];
+    d += partial[((size_t)tile * kGateSlots + sl) * 2 + 1];
+  }
+  s_num[threadIdx.x] = n;
+  s_den[threadIdx.x] = d;
+  __syncthreads();
+  for (int off = kFinalThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      s_num[threadIdx.x] += s_num[threadIdx.x + off];
+      s_den[threadIdx.x] += s_den[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    float change = 0.f;   // first step of a tile: nothing to compare with
+    if (has_prev[tile]) change = s_den[0] > 0.0 ? (float)(s_num[0] / s_den[0]) : __builtin_inff();
+    const float L = path_len[tile] + change;
+    path_len[tile] = L;
+    step_change[tile] = change;
+    const bool known = has_gain[tile] != 0;
+    const float score = known ? gain[tile] * L : __builtin_inff();
+    const float thr = tile_thresholds ? tile_thresholds[tile] : threshold;
+    scores[tile] = score;
+    recompute[tile] = (known && score < thr) ? 0 : 1;   // a NaN score recomputes
+  }
+}
+
+constexpr int kRefreshTilesPerLaunch = 32;
+struct GainPtrs {
+  void* out_cur[kRefreshTilesPerLaunch];
+  const void* out_prev[kRefreshTilesPerLaunch];
+  const void* latent[kRefreshTilesPerLaunch];
+  float* delta[kRefreshTilesPerLaunch];
+};
+
+// One pass over every tile's output after the Denoising Engine ran on the tiles to recompute:
+//   recomputed tile: delta_c = O_t - I_t (fp32) is stored and, if a previous output exists, the sums of
+//                    ||O_t - O_{t-1}||_1 and ||O_{t-1}||_1 are taken in the same pass (O_t is read once);
+//   reused tile:     O_t = I_t + delta_c is written (Residual Approximation).
+// Same streaming layout as the gate: one workgroup per compute unit, equal contiguous slabs per tile.
+// delta is kept in fp32: its magnitude follows the latent's and can exceed the output's by orders, so
+// the output's storage type would lose O_c.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, const uint8_t* __restrict__ recompute,
+                                                                const uint8_t* __restrict__ has_prev, int tile0, int n_tiles,
+                                                                int64_t elems, double* __restrict__ partial) {
+  constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
+  const int blk = blockIdx.x, n_blk = gridDim.x;
+  const int64_t n_vec = elems / kPerVec;
+  const int64_t per_blk = (n_vec + n_blk - 1) / n_blk;
+  const int64_t v0 = (int64_t)blk * per_blk;
+  const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
+  __shared__ double s_num[2][kThreads / 64], s_den[2][kThreads / 64];
+  int par = 0;
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk) * 2;
+    u32x4* __restrict__ oc = (u32x4*)ptrs.out_cur[tile];
+    const u32x4* __restrict__ lat = (const u32x4*)ptrs.latent[tile];
+    u32x4* __restrict__ dl = (u32x4*)ptrs.delta[tile];
+    if (!recompute[tile0 + tile]) {   // reuse: O_t = I_t + delta_c
+      for (int64_t i = v0 + threadIdx.x; i < v1; i += kThreads) {
+        const u32x4 l = __builtin_nontemporal_load(lat + i);
+        u32x4 o;
+        if (DT == SG_BF16) {
+          const u32x4 d0 = __builtin_nontemporal_load(dl + 2 * i), d1 = __builtin_nontemporal_load(dl + 2 * i + 1);
+          o[0] = pack_bf16x2(bf16_bits_to_f32(l[0] & 0xffffu) + __uint_as_float(d0[0]), __uint_as_float(l[0] & 0xffff0000u) + __uint_as_float(d0[1]));
+          o[1] = pack_bf16x2(bf16_bits_to_f32(l[1] & 0xffffu) + __uint_as_float(d0[2]), __uint_as_float(l[1] & 0xffff0000u) + __uint_as_float(d0[3]));
+          o[2] = pack_bf16x2(bf16_bits_to_f32(l[2] & 0xffffu) + __uint_as_float(d1[0]), __uint_as_float(l[2] & 0xffff0000u) + __uint_as_float(d1[1]));
+          o[3] = pack_bf16x2(bf16_bits_to_f32(l[3] & 0xffffu) + __uint_as_float(d1[2]), __uint_as_float(l[3] & 0xffff0000u) + __uint_as_float(d1[3]));
+        } else {
+          const u32x4 d0 = __builtin_nontemporal_load(dl + i);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(l[c]) + __uint_as_float(d0[c]));
+        }
+        __builtin_nontemporal_store(o, oc + i);
+      }
+      if (threadIdx.x == 0) { out[0] = 0.0; out[1] = 0.0; }
+      continue;
+    }
+    // recompute: store the residual; relative change of the output against the previous step's
+    const bool sums = has_prev[tile0 + tile] != 0;
+    const u32x4* __restrict__ op = (const u32x4*)ptrs.out_prev[tile];
+    float num0 = 0.f, den0 = 0.f, num1 = 0.f, den1 = 0.f;
+    for (int64_t i = v0 + threadIdx.x; i < v1; i += kThreads) {
+      const u32x4 a = __builtin_nontemporal_load((const u32x4*)oc + i);
+      const u32x4 l = __builtin_nontemporal_load(lat + i);
+      if (sums) {
+        const u32x4 b = __builtin_nontemporal_load(op + i);
+        if (i & 1) accum_vec<DT>(a, b, num1, den1); else accum_vec<DT>(a, b, num0, den0);
+      }
+      if (DT == SG_BF16) {
+        u32x4 d0, d1;
+        d0[0] = __float_as_uint(bf16_bits_to_f32(a[0] & 0xffffu) - bf16_bits_to_f32(l[0] & 0xffffu));
+        d0[1] = __float_as_uint(__uint_as_float(a[0] & 0xffff0000u) - __uint_as_float(l[0] & 0xffff0000u));
+        d0[2] = __float_as_uint(bf16_bits_to_f32(a[1] & 0xffffu) - bf16_bits_to_f32(l[1] & 0xffffu));
+        d0[3] = __float_as_uint(__uint_as_float(a[1] & 0xffff0000u) - __uint_as_float(l[1] & 0xffff0000u));
+        d1[0] = __float_as_uint(bf16_bits_to_f32(a[2] & 0xffffu) - bf16_bits_to_f32(l[2] & 0xffffu));
+        d1[1] = __float_as_uint(__uint_as_float(a[2] & 0xffff0000u) - __uint_as_float(l[2] & 0xffff0000u));
+        d1[2] = __float_as_uint(bf16_bits_to_f32(a[3] & 0xffffu) - bf16_bits_to_f32(l[3] & 0xffffu));
+        d1[3] = __float_as_uint(__uint_as_float(a[3] & 0xffff0000u) - __uint_as_float(l[3] & 0xffff0000u));
+        __builtin_nontemporal_store(d0, dl + 2 * i);
+        __builtin_nontemporal_store(d1, dl + 2 * i + 1);
+      } else {
+        u32x4 d0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) d0[c] = __float_as_uint(__uint_as_float(a[c]) - __uint_as_float(l[c]));
+        __builtin_nontemporal_store(d0, dl + i);
+      }
+    }
+    double num = (double)num0 + (double)num1, den = (double)den0 + (double)den1;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      num += __shfl_down(num, off, 64);
+      den += __shfl_down(den, off, 64);
+    }
+    if ((threadIdx.x & 63) == 0) { s_num[par][threadIdx.x >> 6] = num; s_den[par][threadIdx.x >> 6] = den; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double n = 0.0, d = 0.0;
+      for (int w = 0; w < kThreads / 64; ++w) { n += s_num[par][w]; d += s_den[par][w]; }
+      out[0] = n;
+      out[1] = d;
+    }
+    par ^= 1;
+  }
+}
+
+// Cache Store update, one workgroup per tile: a recomputed tile gets g_c = ||O_t - O_{t-1}|| / d_t when a
+// previous output exists and d_t is finite and positive (otherwise g_c keeps its state) and L = 0; every
+// tile now has a previous step.
+__global__ __launch_bounds__(kFinalThreads) void gain_refresh_finalize_kernel(
+    const double* __restrict__ partial, int n_slots, const uint8_t* __restrict__ recompute,
+    const float* __restrict__ step_change, uint8_t* __restrict__ has_prev, uint8_t* __restrict__ has_gain,
+    float* __restrict__ gain, float* __restrict__ path_len) {
+  const int tile = blockIdx.x;
+  __shared__ double s_num[kFinalThreads], s_den[kFinalThreads];
+  double n = 0.0, d = 0.0;
+  for (int sl = threadIdx.x; sl < n_slots; sl += kFinalThreads) {
+    n += partial[((size_t)tile * kGateSlots + sl) * 2];
+    d += partial[((size_t)tile * kGateSlots + sl) * 2 + 1];
+  }
+  s_num[threadIdx.x] = n;
+  s_den[threadIdx.x] = d;
+  __syncthreads();
+  for (int off = kFinalThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      s_num[threadIdx.x] += s_num[threadIdx.x + off];
+      s_den[threadIdx.x] += s_den[threadIdx.x + off];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (recompute[tile]) {
+      const float dt = step_change[tile];
+      if (has_prev[tile] && dt > 0.f && dt < __builtin_inff()) {
+        const double r = s_den[0] > 0.0 ? s_num[0] / s_den[0] : (double)__builtin_inff();
+        gain[tile] = (float)(r / (double)dt);
+        has_gain[tile] = 1;
+      }
+      path_len[tile] = 0.f;
+    }
+    has_prev[tile] = 1;
+  }
+}
+
 }  // namespace
 
-int launch_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache, int n_tiles,
-                int64_t elems, int dtype, float threshold, float* scores, uint8_t* recompute, void* ws, hipStream_t s) {
-  if (n_tiles == 0) return SG_OK;
-  double* partial = (double*)ws;
+// Stage 1 for `n_tiles` pairs of buffers: per tile and workgroup one (sum|a-b|, sum|b|) pair in `partial`;
+// tiles whose `active` byte is 0 are not read and get zero sums.  Returns the number of workgroups
+// (= partial pairs per tile) in *n_slots.
+static int launch_partials(const void* const* a, const void* const* b, const uint8_t* active, int n_tiles,
+                           int64_t elems, int dtype, double* partial, int* n_slots, hipStream_t s) {
   // one workgroup per compute unit; the partial-sum layout (and with it the summation order) depends only
   // on the device's compute-unit count
   int dev = 0, n_cu = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots ? kGateSlots : n_cu);
+  *n_slots = n_blk;
   for (int t0 = 0; t0 < n_tiles; t0 += kTilesPerLaunch) {
     const int n = (n_tiles - t0 < kTilesPerLaunch) ? n_tiles - t0 : kTilesPerLaunch;
     GatePtrs ptrs;
-    for (int i = 0; i < n; ++i) { ptrs.cur[i] = x_cur[t0 + i]; ptrs.cached[i] = x_cached[t0 + i]; }
+    for (int i = 0; i < n; ++i) { ptrs.cur[i] = a[t0 + i]; ptrs.cached[i] = b[t0 + i]; }
     for (int i = n; i < kTilesPerLaunch; ++i) { ptrs.cur[i] = nullptr; ptrs.cached[i] = nullptr; }
     if (dtype == SG_BF16)
-      gate_partial_kernel<SG_BF16><<<n_blk, kThreads, 0, s>>>(ptrs, has_cache, t0, n, elems, partial);
+      gate_partial_kernel<SG_BF16><<<n_blk, kThreads, 0, s>>>(ptrs, active, t0, n, elems, partial);
     else
-      gate_partial_kernel<SG_F32><<<n_blk, kThreads, 0, s>>>(ptrs, has_cache, t0, n, elems, partial);
+      gate_partial_kernel<SG_F32><<<n_blk, kThreads, 0, s>>>(ptrs, active, t0, n, elems, partial);
     SG_HIP_TRY(hipGetLastError());
   }
+  return SG_OK;
+}
+
+int launch_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache, int n_tiles,
+                int64_t elems, int dtype, float threshold, float* scores, uint8_t* recompute, void* ws, hipStream_t s) {
+  if (n_tiles == 0) return SG_OK;
+  double* partial = (double*)ws;
+  int n_blk = 0;
+  const int st = launch_partials(x_cur, x_cached, has_cache, n_tiles, elems, dtype, partial, &n_blk, s);
+  if (st != SG_OK) return st;
   gate_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk, has_cache, threshold, scores, recompute);
+  SG_HIP_TRY(hipGetLastError());
+  return SG_OK;
+}
+
+int launch_gain_gate(const void* const* x_cur, const void* const* x_prev, const sg_gain_state& gs, int n_tiles,
+                     int64_t elems, int dtype, float threshold, const float* tile_thresholds, float* step_change,
+                     float* scores, uint8_t* recompute, void* ws, hipStream_t s) {
+  if (n_tiles == 0) return SG_OK;
+  double* partial = (double*)ws;
+  int n_blk = 0;
+  const int st = launch_partials(x_cur, x_prev, gs.has_prev, n_tiles, elems, dtype, partial, &n_blk, s);
+  if (st != SG_OK) return st;
+  gain_gate_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk, gs.has_prev, gs.has_gain, gs.gain,
+                                                              gs.path_len, threshold, tile_thresholds, step_change,
+                                                              scores, recompute);
+  SG_HIP_TRY(hipGetLastError());
+  return SG_OK;
+}
+
+int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const void* const* latent,
+                        float* const* delta, const uint8_t* recompute, const float* step_change,
+                        const sg_gain_state& gs, int n_tiles, int64_t elems, int dtype, void* ws, hipStream_t s) {
+  if (n_tiles == 0) return SG_OK;
+  double* partial = (double*)ws;
+  int dev = 0, n_cu = 0;
+  SG_HIP_TRY(hipGetDevice(&dev));
+  SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots ? kGateSlots : n_cu);
+  for (int t0 = 0; t0 < n_tiles; t0 += kRefreshTilesPerLaunch) {
+    const int n = (n_tiles - t0 < kRefreshTilesPerLaunch) ? n_tiles - t0 : kRefreshTilesPerLaunch;
+    GainPtrs ptrs;
+    for (int i = 0; i < kRefreshTilesPerLaunch; ++i) {
+      ptrs.out_cur[i] = i < n ? out_cur[t0 + i] : nullptr;
+      ptrs.out_prev[i] = i < n ? out_prev[t0 + i] : nullptr;
+      ptrs.latent[i] = i < n ? latent[t0 + i] : nullptr;
+      ptrs.delta[i] = i < n ? delta[t0 + i] : nullptr;
+    }
+    if (dtype == SG_BF16)
+      gain_refresh_kernel<SG_BF16><<<n_blk, kThreads, 0, s>>>(ptrs, recompute, gs.has_prev, t0, n, elems, partial);
+    else
+      gain_refresh_kernel<SG_F32><<<n_blk, kThreads, 0, s>>>(ptrs, recompute, gs.has_prev, t0, n, elems, partial);
+    SG_HIP_TRY(hipGetLastError());
+  }
+  gain_refresh_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk, recompute, step_change, gs.has_prev,
+                                                                 gs.has_gain, gs.gain, gs.path_len);
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }

@@ -180,4 +180,87 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, s);
 }
 
+static int check_gain_state(const sg_gain_state* st) {
+  if (!st || !st->has_prev || !st->has_gain || !st->gain || !st->path_len) return SG_ERR_INVALID_ARG;
+  return SG_OK;
+}
+static int check_ptr_array(const void* const* a, int n) {
+  if (!a) return SG_ERR_INVALID_ARG;
+  for (int i = 0; i < n; ++i)
+    if (!a[i] || !aligned16(a[i])) return SG_ERR_INVALID_ARG;
+  return SG_OK;
+}
+
+int sg_gain_gate(const void* const* x_cur, const void* const* x_prev, const sg_gain_state* state, int32_t n_tiles,
+                 int64_t elems_per_tile, int32_t dtype, float threshold, const float* tile_thresholds,
+                 float* step_change, float* scores, uint8_t* recompute, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  if (n_tiles < 0 || elems_per_tile < 0) return SG_ERR_INVALID_ARG;
+  if (dtype != SG_F32 && dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (std::isnan(threshold)) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (check_gain_state(state) != SG_OK || !step_change || !scores || !recompute) return SG_ERR_INVALID_ARG;
+  if (check_ptr_array(x_cur, n_tiles) != SG_OK || check_ptr_array(x_prev, n_tiles) != SG_OK) return SG_ERR_INVALID_ARG;
+  if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  return launch_gain_gate(x_cur, x_prev, *state, n_tiles, elems_per_tile, dtype, threshold, tile_thresholds,
+                          step_change, scores, recompute, workspace, (hipStream_t)stream);
+}
+
+int sg_gain_refresh(void* const* out_cur, const void* const* out_prev, const void* const* latent, float* const* delta,
+                    const uint8_t* recompute, const float* step_change, const sg_gain_state* state, int32_t n_tiles,
+                    int64_t elems_per_tile, int32_t dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_tiles < 0 || elems_per_tile < 0 || (elems_per_tile & 7)) return SG_ERR_INVALID_ARG;
+  if (dtype != SG_F32 && dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (check_gain_state(state) != SG_OK || !recompute || !step_change) return SG_ERR_INVALID_ARG;
+  if (check_ptr_array((const void* const*)out_cur, n_tiles) != SG_OK || check_ptr_array(out_prev, n_tiles) != SG_OK ||
+      check_ptr_array(latent, n_tiles) != SG_OK || check_ptr_array((const void* const*)delta, n_tiles) != SG_OK)
+    return SG_ERR_INVALID_ARG;
+  if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  return launch_gain_refresh(out_cur, out_prev, latent, delta, recompute, step_change, *state, n_tiles, elems_per_tile,
+                             dtype, workspace, (hipStream_t)stream);
+}
+
+int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!io || !io->grid_out || !aligned16(io->grid_out)) return SG_ERR_INVALID_ARG;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
+  if (check_gain_state(&io->state) != SG_OK || !io->step_change || !io->scores || !io->recompute)
+    return SG_ERR_INVALID_ARG;
+  if (std::isnan(io->threshold)) return SG_ERR_INVALID_ARG;
+  if (check_ptr_array(io->tile_x, n_tiles) != SG_OK || check_ptr_array(io->prev_x, n_tiles) != SG_OK ||
+      check_ptr_array((const void* const*)io->out_cur, n_tiles) != SG_OK ||
+      check_ptr_array(io->out_prev, n_tiles) != SG_OK || check_ptr_array((const void* const*)io->delta, n_tiles) != SG_OK)
+    return SG_ERR_INVALID_ARG;
+  if (io->latent && check_ptr_array(io->latent, n_tiles) != SG_OK) return SG_ERR_INVALID_ARG;
+  if (!io->workspace || (((uintptr_t)io->workspace) & 255u) || io->workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t esz = p->dtype == SG_BF16 ? 2 : 4;
+  const int64_t tile_elems = (int64_t)p->heads * p->T * p->tile_h * p->tile_w * p->head_dim;
+
+  st = launch_gain_gate(io->tile_x, io->prev_x, io->state, n_tiles, 3 * tile_elems, p->dtype, io->threshold,
+                        io->tile_thresholds, io->step_change, io->scores, io->recompute, io->workspace, s);
+  if (st != SG_OK) return st;
+  sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
+  tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+  tp.grid_stride_token = p->head_dim;
+  tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
+  const TileView tv = make_view(tp, 0, 0);
+  for (int i = 0; i < n_tiles; ++i) {
+    const char* x = (const char*)io->tile_x[i];
+    st = attention_dispatch(tp, tv, x, x + tile_elems * esz, x + 2 * tile_elems * esz, io->out_cur[i],
+                            io->recompute + i, s);
+    if (st != SG_OK) return st;
+  }
+  // the residual is taken against the Q part of the packed input unless the caller names a latent
+  st = launch_gain_refresh(io->out_cur, io->out_prev, io->latent ? io->latent : io->tile_x, io->delta, io->recompute,
+                           io->step_change, io->state, n_tiles, tile_elems, p->dtype, io->workspace, s);
+  if (st != SG_OK) return st;
+  return launch_blend(*p, (const void* const*)io->out_cur, io->grid_out, s);
+}
+
 }  // extern "C"

@@ -38,6 +38,12 @@ int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_ou
 int launch_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache,
                 int n_tiles, int64_t elems, int dtype, float threshold, float* scores,
                 uint8_t* recompute, void* ws, hipStream_t s);
+int launch_gain_gate(const void* const* x_cur, const void* const* x_prev, const sg_gain_state& gs, int n_tiles,
+                     int64_t elems, int dtype, float threshold, const float* tile_thresholds, float* step_change,
+                     float* scores, uint8_t* recompute, void* ws, hipStream_t s);
+int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const void* const* latent,
+                        float* const* delta, const uint8_t* recompute, const float* step_change,
+                        const sg_gain_state& gs, int n_tiles, int64_t elems, int dtype, void* ws, hipStream_t s);
 int launch_cache_refresh(const void* const* src, void* const* dst, const uint8_t* recompute,
                          uint8_t* has_cache, int n_tiles, int64_t bytes_per_tile, hipStream_t s);
 

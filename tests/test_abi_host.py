@@ -62,3 +62,14 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_cache_gate(arr, arr, 256, 2, 64, 9, 0.05, 256, 256, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_denoise_step_tiled(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG
     assert sg.sg_workspace_bytes(20) >= 20 * 2 * 8
+    # gain / path-length policy entry points
+    st = sg.sg_gain_state()
+    st.has_prev = st.has_gain = st.gain = st.path_len = 256
+    assert lib.sg_gain_gate(arr, arr, None, 2, 64, sg.SG_BF16, 0.05, None, 256, 256, 256, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_gain_gate(arr, arr, ctypes.byref(st), 2, 64, sg.SG_BF16, 0.05, None, 256, 256, 256, None, 0, None) == sg.SG_ERR_WORKSPACE
+    assert lib.sg_gain_gate(arr, arr, ctypes.byref(st), 2, 64, sg.SG_BF16, float("nan"), None, 256, 256, 256, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_gain_gate(arr, arr, ctypes.byref(st), 0, 64, sg.SG_BF16, 0.05, None, None, None, None, None, 0, None) == sg.SG_OK
+    assert lib.sg_gain_refresh(arr, arr, arr, arr, 256, 256, ctypes.byref(st), 2, 63, sg.SG_BF16, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG   # not a multiple of 8
+    assert lib.sg_gain_refresh(arr, arr, arr, None, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_gain_refresh(arr, arr, arr, arr, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 16, None) == sg.SG_ERR_WORKSPACE
+    assert lib.sg_denoise_step_gain(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG

@@ -1,0 +1,205 @@
+"""GPU parity of the inter-step cache policy entry points (sg_gain_gate, sg_gain_refresh,
+sg_denoise_step_gain) against the fp64 oracle on the same stored values."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_17756_amd as sg
+from synthetic import TileGeometry, randn_tensor, torch_dtype, perturb_
+from gpu_util import to_f64, errors, assert_close, BF16_MAX_ABS, BF16_REL_L2
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_state(state, x_prev=None, o_prev=None, delta=None):
+    """fp64 copy of the device state (stored values widened exactly)."""
+    n = state.gain.numel()
+    st = oracle.GainState(n)
+    st.has_prev = [bool(v) for v in state.has_prev.cpu().numpy()]
+    st.has_gain = [bool(v) for v in state.has_gain.cpu().numpy()]
+    st.gain = [float(v) for v in state.gain.cpu().numpy().astype(np.float64)]
+    st.path_len = [float(v) for v in state.path_len.cpu().numpy().astype(np.float64)]
+    if x_prev is not None:
+        st.x_prev = [to_f64(t).ravel() for t in x_prev]
+    if o_prev is not None:
+        st.o_prev = [to_f64(t) for t in o_prev]
+    if delta is not None:
+        st.delta = [to_f64(t) for t in delta]
+    return st
+
+
+def _close(a, b, rel=2e-6):
+    a, b = float(a), float(b)
+    if np.isinf(b) or np.isinf(a):
+        return a == b
+    return abs(a - b) <= rel * max(1.0, abs(b))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("elems", [64, 4096 + 8, 3 * 2 * 3 * 10 * 10 * 64, 1 << 20])
+@pytest.mark.parametrize("per_tile_thr", [False, True])
+def test_gain_gate_small(dtype, elems, per_tile_thr):
+    n = 6
+    prev = [randn_tensor((elems,), dtype, 100 + i).cuda() for i in range(n)]
+    eps = [0.0, 0.01, 0.1, 0.03, 0.02, 0.05]
+    cur = [perturb_(c.clone(), e, 200 + i) for i, (c, e) in enumerate(zip(prev, eps))]
+    prev[5].zero_()                                               # zero denominator: d = +inf
+    state = sg.GainState(n)
+    state.has_prev.copy_(torch.tensor([1, 1, 1, 0, 1, 1], dtype=torch.uint8))
+    state.has_gain.copy_(torch.tensor([1, 1, 1, 1, 0, 1], dtype=torch.uint8))
+    state.gain.copy_(torch.tensor([2.0, 1.5, 0.4, 1.0, 3.0, 1.0]))
+    state.path_len.copy_(torch.tensor([0.01, 0.02, 0.0, 0.125, 0.5, 0.0]))
+    thr = torch.tensor([0.05, 0.04, 0.05, 0.2, 0.05, 0.05], dtype=torch.float32, device="cuda")
+    ref_state = _oracle_state(state, x_prev=prev)
+    d_ref, s_ref, r_ref = oracle.gain_gate([to_f64(t) for t in cur], ref_state,
+                                           [float(v) for v in thr.cpu().numpy().astype(np.float64)] if per_tile_thr
+                                           else [float(np.float32(0.05))] * n)
+    step = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+    scores = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+    rec = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    sg.sg_gain_gate(cur, prev, state, 0.05, step, scores, rec, ws, tile_thresholds=thr if per_tile_thr else None)
+    torch.cuda.synchronize()
+    d, s, r, L = (t.cpu().numpy() for t in (step, scores, rec, state.path_len))
+    for i in range(n):
+        assert _close(d[i], d_ref[i]), (i, d[i], d_ref[i])
+        assert _close(L[i], ref_state.path_len[i]), (i, L[i], ref_state.path_len[i])
+        assert _close(s[i], s_ref[i]), (i, s[i], s_ref[i])
+        t_i = float(thr[i]) if per_tile_thr else float(np.float32(0.05))
+        if np.isinf(s_ref[i]) or abs(s_ref[i] - t_i) > 1e-4:
+            assert bool(r[i]) == bool(r_ref[i]), (i, s[i], s_ref[i])
+    assert d[0] == 0.0 and d[3] == 0.0 and np.isinf(d[5])        # identical input; no previous step; zero denominator
+    assert r[4] == 1 and np.isinf(s[4])                           # gain unknown: recompute
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("elems", [64, 8 * 1031, 2 * 3 * 10 * 10 * 64, 1 << 20])
+def test_gain_refresh_small(dtype, elems):
+    n = 5
+    td = torch_dtype(dtype)
+    out_prev = [randn_tensor((elems,), dtype, 300 + i).cuda() for i in range(n)]
+    out_new = [perturb_(o.clone(), 0.05 * (i + 1), 400 + i) for i, o in enumerate(out_prev)]
+    latent = [randn_tensor((elems,), dtype, 500 + i).cuda() for i in range(n)]
+    delta = [randn_tensor((elems,), "f32", 600 + i).cuda() * 0.01 for i in range(n)]
+    out_cur = [o.clone() for o in out_new]
+    rec = torch.tensor([1, 0, 1, 1, 1], dtype=torch.uint8, device="cuda")
+    step = torch.tensor([0.02, 0.5, 0.03, 0.0, float("inf")], dtype=torch.float32, device="cuda")
+    state = sg.GainState(n)
+    state.has_prev.copy_(torch.tensor([1, 1, 0, 1, 1], dtype=torch.uint8))
+    state.has_gain.copy_(torch.tensor([0, 1, 0, 1, 1], dtype=torch.uint8))
+    state.gain.copy_(torch.tensor([0.0, 1.5, 0.0, 0.75, 2.0]))
+    state.path_len.copy_(torch.tensor([0.3, 0.04, 0.0, 0.2, 0.1]))
+    ref_state = _oracle_state(state, o_prev=out_prev, delta=delta)
+    ref_outs = oracle.gain_refresh([to_f64(t) for t in out_new], [to_f64(t) for t in latent],
+                                   rec.cpu().numpy().astype(bool), step.cpu().numpy().astype(np.float64), ref_state)
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    sg.sg_gain_refresh(out_cur, out_prev, latent, delta, rec, step, state, ws)
+    torch.cuda.synchronize()
+    g, L = state.gain.cpu().numpy(), state.path_len.cpu().numpy()
+    assert state.has_prev.cpu().tolist() == [1] * n
+    # tile 0: gain from the outputs; tile 2: no previous step, tile 3: d = 0, tile 4: d = inf -> gain keeps its state
+    assert state.has_gain.cpu().tolist() == [1, 1, 0, 1, 1] == [int(v) for v in ref_state.has_gain]
+    for i in range(n):
+        assert _close(g[i], ref_state.gain[i], rel=1e-5), (i, g[i], ref_state.gain[i])
+        assert L[i] == np.float32(ref_state.path_len[i])
+        if rec[i]:
+            assert torch.equal(out_cur[i], out_new[i])                       # the engine's output is left as it is
+            np.testing.assert_allclose(to_f64(delta[i]), ref_state.delta[i], rtol=0, atol=1e-6)
+        else:
+            assert_close(to_f64(out_cur[i]), ref_outs[i], dtype, f"reused tile {i}")
+    assert L[1] == np.float32(0.04) and L[0] == 0.0
+
+
+def _geom(name, T, H, W, th, tw, sh, sw, heads, d, dtype, seed):
+    nr = (H - th) // sh + 1 if th < H else 1
+    nc = (W - tw) // sw + 1 if tw < W else 1
+    return TileGeometry(name, T, H, W, th, tw, sh, sw, nr, nc, heads, d, dtype, seed)
+
+
+def _bf16_round(a):
+    return torch.from_numpy(np.asarray(a)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def test_step_gain_chain_bf16():
+    """Seven steps of a 2 x 2 tiling under the policy.  After every step the oracle takes the same step
+    from the same stored state, with the GPU's stored attention outputs standing in for its engine (those
+    are checked against the oracle's own attention separately), so gate, gain, residual and reuse are
+    compared tightly step by step."""
+    g = _geom("gainc", 2, 14, 20, 8, 12, 6, 8, 2, 128, "bf16", 91)       # N = 192 per tile
+    n = g.n_tiles
+    E = int(np.prod(g.tile_shape))
+    canvas_in = [randn_tensor(g.grid_shape, "bf16", g.seed + 7 * s).cuda() for s in range(3)]
+    x_a = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            r0, c0 = tr * g.stride_h, tc * g.stride_w
+            x_a.append(torch.stack([t[:, :, r0:r0 + g.tile_h, c0:c0 + g.tile_w, :] for t in canvas_in]).contiguous())
+    x_b = [torch.zeros_like(t) for t in x_a]
+    outs = [[torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)]
+    delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)]
+    state = sg.GainState(n)
+    step_change = torch.empty(n, dtype=torch.float32, device="cuda")
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    rec = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    p = sg.make_problem(g)
+    thr = float(np.float32(0.05))
+    eps = [None, [0.02] * 4, [0.002, 0.2, 0.002, 0.2], [0.002, 0.002, 0.2, 0.002], [0.002, 0.002, 0.002, 0.002],
+           [0.2, 0.002, 0.002, 0.002], [0.002, 0.002, 0.002, 0.2]]
+    bufs = [x_a, x_b]
+    ost = oracle.GainState(n)
+    seen_reuse = seen_recompute_late = 0
+    for k in range(len(eps)):
+        cur, prev = bufs[k % 2], bufs[(k + 1) % 2]
+        if k:
+            for i in range(n):
+                cur[i].copy_(prev[i])
+                perturb_(cur[i], eps[k][i], 5000 + 10 * k + i)
+        o_cur, o_prev = outs[k % 2], outs[(k + 1) % 2]
+        sg.sg_denoise_step_gain(p, canvas, cur, prev, o_cur, o_prev, delta, state, 0.05, step_change, scores, rec, ws)
+        torch.cuda.synchronize()
+        r = rec.cpu().numpy().astype(bool)
+        gpu_out = [to_f64(t) for t in o_cur]
+        # the oracle's step from its own state (kept in lockstep through stored values)
+        ref_canvas, d_ref, s_ref, r_ref, ref_outs = oracle.denoise_step_gain(
+            [tuple(to_f64(t[j]) for j in range(3)) for t in cur], g, g.scale, ost, [thr] * n,
+            model=lambda i, Q, K, V: gpu_out[i], store=_bf16_round)
+        d, s = step_change.cpu().numpy(), scores.cpu().numpy()
+        for i in range(n):
+            assert _close(d[i], d_ref[i]), (k, i, d[i], d_ref[i])
+            assert _close(s[i], s_ref[i], rel=1e-4), (k, i, s[i], s_ref[i])
+            if np.isinf(s_ref[i]) or abs(s_ref[i] - thr) > 1e-4:
+                assert r[i] == r_ref[i], (k, i, s[i], s_ref[i])
+        assert list(r) == list(r_ref)
+        print(f"step {k}: d={np.round(d, 4).tolist()} score={np.round(s, 4).tolist()} recompute={r.astype(int).tolist()}")
+        if k < 2:
+            assert r.all()                                        # the gain needs two outputs
+        # engine outputs of recomputed tiles against the oracle's attention
+        for i in range(n):
+            if r[i]:
+                Q, K, V = (to_f64(cur[i][j]) for j in range(3))
+                ref = np.stack([oracle.attention(Q[a].reshape(-1, 128), K[a].reshape(-1, 128), V[a].reshape(-1, 128),
+                                                 g.scale) for a in range(g.heads)]).reshape(g.tile_shape)
+                assert_close(gpu_out[i], ref, "bf16", f"step {k} tile {i}")
+                np.testing.assert_allclose(to_f64(delta[i]).reshape(g.tile_shape), ost.delta[i], rtol=0, atol=1e-6)
+                seen_recompute_late += int(k >= 2)
+            else:
+                # reused: one rounding of latent + delta (the oracle rounds the same sum in fp64)
+                ma, _ = errors(gpu_out[i], ref_outs[i])
+                assert ma <= 2.0 ** -7 * max(1.0, float(np.abs(ref_outs[i]).max())), (k, i, ma)
+                seen_reuse += 1
+        gains, L = state.gain.cpu().numpy(), state.path_len.cpu().numpy()
+        for i in range(n):
+            assert bool(state.has_gain[i]) == ost.has_gain[i]
+            assert _close(gains[i], ost.gain[i], rel=1e-4), (k, i, gains[i], ost.gain[i])
+            assert _close(L[i], ost.path_len[i], rel=1e-5)
+        assert_close(to_f64(canvas), oracle.blend(gpu_out, g), "bf16", f"canvas step {k}")
+        # keep the oracle's state on the stored values exactly
+        for i in range(n):
+            ost.o_prev[i] = gpu_out[i]
+            ost.gain[i] = float(gains[i])
+            ost.path_len[i] = float(L[i])
+            ost.delta[i] = to_f64(delta[i]).reshape(g.tile_shape)
+    assert seen_reuse >= 4 and seen_recompute_late >= 2
