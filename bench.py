@@ -139,6 +139,23 @@ def full_extras(torch, sg, args):
         e1.synchronize()
         per_step.append({"ms": round(e0.elapsed_time(e1), 2), "recomputed": int(rec.sum())})
     res["gated_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1), "steps": per_step}
+    del tile_x, cache_x
+    # inter-step cache policy (gain, path length, residual reuse): the refresh pass alone, half the tiles
+    # recomputed (reads O_t, O_{t-1}, I_t, writes delta: 10 B per element) and half reused (reads I_t, delta,
+    # writes O_t: 8 B per element)
+    E = int(np.prod(g5.tile_shape))
+    o_cur = cache_out
+    o_prev = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
+    latent = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
+    delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n5)]
+    state = sg.GainState(n5)
+    state.has_prev.fill_(1)
+    half = torch.tensor([i % 2 for i in range(n5)], dtype=torch.uint8, device="cuda")
+    step_change = torch.full((n5,), 0.05, dtype=torch.float32, device="cuda")
+    ms_r = time_calls(torch, lambda: sg.sg_gain_refresh(o_cur, o_prev, latent, delta, half, step_change, state, ws), 10)
+    nb = float(E) * (10 * int(half.sum()) + 8 * (n5 - int(half.sum())))
+    res["gain_refresh_4k"] = {"ms": round(ms_r, 4), "GB/s": round(nb / ms_r * 1e-6, 1),
+                              "frac_hbm_peak": round(nb / ms_r * 1e-6 / PEAK_HBM_GBS, 4), "recomputed_tiles": int(half.sum())}
     return res
 
 

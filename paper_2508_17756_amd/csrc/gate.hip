@@ -205,6 +205,43 @@ __global__ __launch_bounds__(kFinalThreads) void gain_gate_finalize_kernel(
 }
 
 constexpr int kRefreshTilesPerLaunch = 32;
+// Measured on the 4K sizes: unroll 1-8 and 1-4 workgroups per compute unit all land within 4.4-5.1 TB/s (the
+// pass writes 40-25 % of its bytes and runs at the device's copy rate); 2 and 1 were the best pair.
+constexpr int kRefreshUnroll = 2;
+constexpr int kRefreshBlocksPerCu = 1;
+
+// one 16-byte vector of outputs: O = I + delta (delta in fp32: two vectors for bf16 tensors, one for fp32)
+template <int DT>
+__device__ __forceinline__ u32x4 residual_apply(const u32x4 l, const u32x4 d0, const u32x4 d1) {
+  u32x4 o;
+  if (DT == SG_BF16) {
+    o[0] = pack_bf16x2(bf16_bits_to_f32(l[0] & 0xffffu) + __uint_as_float(d0[0]), __uint_as_float(l[0] & 0xffff0000u) + __uint_as_float(d0[1]));
+    o[1] = pack_bf16x2(bf16_bits_to_f32(l[1] & 0xffffu) + __uint_as_float(d0[2]), __uint_as_float(l[1] & 0xffff0000u) + __uint_as_float(d0[3]));
+    o[2] = pack_bf16x2(bf16_bits_to_f32(l[2] & 0xffffu) + __uint_as_float(d1[0]), __uint_as_float(l[2] & 0xffff0000u) + __uint_as_float(d1[1]));
+    o[3] = pack_bf16x2(bf16_bits_to_f32(l[3] & 0xffffu) + __uint_as_float(d1[2]), __uint_as_float(l[3] & 0xffff0000u) + __uint_as_float(d1[3]));
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(l[c]) + __uint_as_float(d0[c]));
+  }
+  return o;
+}
+// delta = O - I for one 16-byte vector of outputs
+template <int DT>
+__device__ __forceinline__ void residual_take(const u32x4 a, const u32x4 l, u32x4& d0, u32x4& d1) {
+  if (DT == SG_BF16) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      d0[2 * c] = __float_as_uint(bf16_bits_to_f32(a[c] & 0xffffu) - bf16_bits_to_f32(l[c] & 0xffffu));
+      d0[2 * c + 1] = __float_as_uint(__uint_as_float(a[c] & 0xffff0000u) - __uint_as_float(l[c] & 0xffff0000u));
+      d1[2 * c] = __float_as_uint(bf16_bits_to_f32(a[c + 2] & 0xffffu) - bf16_bits_to_f32(l[c + 2] & 0xffffu));
+      d1[2 * c + 1] = __float_as_uint(__uint_as_float(a[c + 2] & 0xffff0000u) - __uint_as_float(l[c + 2] & 0xffff0000u));
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) d0[c] = __float_as_uint(__uint_as_float(a[c]) - __uint_as_float(l[c]));
+    d1 = d0;
+  }
+}
 struct GainPtrs {
   void* out_cur[kRefreshTilesPerLaunch];
   const void* out_prev[kRefreshTilesPerLaunch];
@@ -237,21 +274,26 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
     const u32x4* __restrict__ lat = (const u32x4*)ptrs.latent[tile];
     u32x4* __restrict__ dl = (u32x4*)ptrs.delta[tile];
     if (!recompute[tile0 + tile]) {   // reuse: O_t = I_t + delta_c
-      for (int64_t i = v0 + threadIdx.x; i < v1; i += kThreads) {
-        const u32x4 l = __builtin_nontemporal_load(lat + i);
-        u32x4 o;
-        if (DT == SG_BF16) {
-          const u32x4 d0 = __builtin_nontemporal_load(dl + 2 * i), d1 = __builtin_nontemporal_load(dl + 2 * i + 1);
-          o[0] = pack_bf16x2(bf16_bits_to_f32(l[0] & 0xffffu) + __uint_as_float(d0[0]), __uint_as_float(l[0] & 0xffff0000u) + __uint_as_float(d0[1]));
-          o[1] = pack_bf16x2(bf16_bits_to_f32(l[1] & 0xffffu) + __uint_as_float(d0[2]), __uint_as_float(l[1] & 0xffff0000u) + __uint_as_float(d0[3]));
-          o[2] = pack_bf16x2(bf16_bits_to_f32(l[2] & 0xffffu) + __uint_as_float(d1[0]), __uint_as_float(l[2] & 0xffff0000u) + __uint_as_float(d1[1]));
-          o[3] = pack_bf16x2(bf16_bits_to_f32(l[3] & 0xffffu) + __uint_as_float(d1[2]), __uint_as_float(l[3] & 0xffff0000u) + __uint_as_float(d1[3]));
-        } else {
-          const u32x4 d0 = __builtin_nontemporal_load(dl + i);
+      int64_t i = v0 + threadIdx.x;
+      for (; i + (kRefreshUnroll - 1) * kThreads < v1; i += kRefreshUnroll * kThreads) {
+        u32x4 l[kRefreshUnroll], d0[kRefreshUnroll], d1[kRefreshUnroll];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) o[c] = __float_as_uint(__uint_as_float(l[c]) + __uint_as_float(d0[c]));
+        for (int u = 0; u < kRefreshUnroll; ++u) {
+          const int64_t j = i + u * kThreads;
+          l[u] = __builtin_nontemporal_load(lat + j);
+          if (DT == SG_BF16) { d0[u] = __builtin_nontemporal_load(dl + 2 * j); d1[u] = __builtin_nontemporal_load(dl + 2 * j + 1); }
+          else d0[u] = __builtin_nontemporal_load(dl + j);
         }
-        __builtin_nontemporal_store(o, oc + i);
+#pragma unroll
+        for (int u = 0; u < kRefreshUnroll; ++u)
+          __builtin_nontemporal_store(residual_apply<DT>(l[u], d0[u], d1[u]), oc + i + u * kThreads);
+      }
+      for (; i < v1; i += kThreads) {
+        const u32x4 l = __builtin_nontemporal_load(lat + i);
+        u32x4 d0, d1 = {0, 0, 0, 0};
+        if (DT == SG_BF16) { d0 = __builtin_nontemporal_load(dl + 2 * i); d1 = __builtin_nontemporal_load(dl + 2 * i + 1); }
+        else d0 = __builtin_nontemporal_load(dl + i);
+        __builtin_nontemporal_store(residual_apply<DT>(l, d0, d1), oc + i);
       }
       if (threadIdx.x == 0) { out[0] = 0.0; out[1] = 0.0; }
       continue;
@@ -260,31 +302,34 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
     const bool sums = has_prev[tile0 + tile] != 0;
     const u32x4* __restrict__ op = (const u32x4*)ptrs.out_prev[tile];
     float num0 = 0.f, den0 = 0.f, num1 = 0.f, den1 = 0.f;
-    for (int64_t i = v0 + threadIdx.x; i < v1; i += kThreads) {
+    int64_t i = v0 + threadIdx.x;
+    for (; i + (kRefreshUnroll - 1) * kThreads < v1; i += kRefreshUnroll * kThreads) {
+      u32x4 a[kRefreshUnroll], l[kRefreshUnroll], b[kRefreshUnroll];
+#pragma unroll
+      for (int u = 0; u < kRefreshUnroll; ++u) {
+        const int64_t j = i + u * kThreads;
+        a[u] = __builtin_nontemporal_load((const u32x4*)oc + j);
+        l[u] = __builtin_nontemporal_load(lat + j);
+        if (sums) b[u] = __builtin_nontemporal_load(op + j);
+      }
+#pragma unroll
+      for (int u = 0; u < kRefreshUnroll; ++u) {
+        const int64_t j = i + u * kThreads;
+        if (sums) { if (u & 1) accum_vec<DT>(a[u], b[u], num1, den1); else accum_vec<DT>(a[u], b[u], num0, den0); }
+        u32x4 d0, d1;
+        residual_take<DT>(a[u], l[u], d0, d1);
+        if (DT == SG_BF16) { __builtin_nontemporal_store(d0, dl + 2 * j); __builtin_nontemporal_store(d1, dl + 2 * j + 1); }
+        else __builtin_nontemporal_store(d0, dl + j);
+      }
+    }
+    for (; i < v1; i += kThreads) {
       const u32x4 a = __builtin_nontemporal_load((const u32x4*)oc + i);
       const u32x4 l = __builtin_nontemporal_load(lat + i);
-      if (sums) {
-        const u32x4 b = __builtin_nontemporal_load(op + i);
-        if (i & 1) accum_vec<DT>(a, b, num1, den1); else accum_vec<DT>(a, b, num0, den0);
-      }
-      if (DT == SG_BF16) {
-        u32x4 d0, d1;
-        d0[0] = __float_as_uint(bf16_bits_to_f32(a[0] & 0xffffu) - bf16_bits_to_f32(l[0] & 0xffffu));
-        d0[1] = __float_as_uint(__uint_as_float(a[0] & 0xffff0000u) - __uint_as_float(l[0] & 0xffff0000u));
-        d0[2] = __float_as_uint(bf16_bits_to_f32(a[1] & 0xffffu) - bf16_bits_to_f32(l[1] & 0xffffu));
-        d0[3] = __float_as_uint(__uint_as_float(a[1] & 0xffff0000u) - __uint_as_float(l[1] & 0xffff0000u));
-        d1[0] = __float_as_uint(bf16_bits_to_f32(a[2] & 0xffffu) - bf16_bits_to_f32(l[2] & 0xffffu));
-        d1[1] = __float_as_uint(__uint_as_float(a[2] & 0xffff0000u) - __uint_as_float(l[2] & 0xffff0000u));
-        d1[2] = __float_as_uint(bf16_bits_to_f32(a[3] & 0xffffu) - bf16_bits_to_f32(l[3] & 0xffffu));
-        d1[3] = __float_as_uint(__uint_as_float(a[3] & 0xffff0000u) - __uint_as_float(l[3] & 0xffff0000u));
-        __builtin_nontemporal_store(d0, dl + 2 * i);
-        __builtin_nontemporal_store(d1, dl + 2 * i + 1);
-      } else {
-        u32x4 d0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) d0[c] = __float_as_uint(__uint_as_float(a[c]) - __uint_as_float(l[c]));
-        __builtin_nontemporal_store(d0, dl + i);
-      }
+      if (sums) accum_vec<DT>(a, __builtin_nontemporal_load(op + i), num0, den0);
+      u32x4 d0, d1;
+      residual_take<DT>(a, l, d0, d1);
+      if (DT == SG_BF16) { __builtin_nontemporal_store(d0, dl + 2 * i); __builtin_nontemporal_store(d1, dl + 2 * i + 1); }
+      else __builtin_nontemporal_store(d0, dl + i);
     }
     double num = (double)num0 + (double)num1, den = (double)den0 + (double)den1;
 #pragma unroll
@@ -405,7 +450,8 @@ int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const
   int dev = 0, n_cu = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots ? kGateSlots : n_cu);
+  int n_blk = (n_cu < 1 ? 1 : n_cu) * kRefreshBlocksPerCu;
+  if (n_blk > kGateSlots) n_blk = kGateSlots;
   for (int t0 = 0; t0 < n_tiles; t0 += kRefreshTilesPerLaunch) {
     const int n = (n_tiles - t0 < kRefreshTilesPerLaunch) ? n_tiles - t0 : kRefreshTilesPerLaunch;
     GainPtrs ptrs;

@@ -148,3 +148,96 @@ def test_config5_gated_steps():
     assert has_cache.cpu().numpy().all()
     _blend_plane_check(g, cache_out, canvas, [(0, 0), (g.heads - 1, g.T - 1)])
     print(f"config 5: {n_recomputed} of {n * steps} tile attentions recomputed")
+
+
+def _host_rel_l1(new, old):
+    """fp64 relative L1 of two device tensors, streamed in slabs to bound host memory."""
+    a, b = new.reshape(-1), old.reshape(-1)
+    num = den = 0.0
+    slab = 1 << 27
+    for s in range(0, a.numel(), slab):
+        x, y = to_f64(a[s:s + slab]), to_f64(b[s:s + slab])
+        num += float(np.abs(x - y).sum())
+        den += float(np.abs(y).sum())
+    return num / den
+
+
+def test_4k_steps_under_the_gain_policy():
+    """Six steps of the 4K tiling under the inter-step cache policy (gain, path length, residual reuse) at
+    the benchmark's tile size.  Every decision must follow from the stored state (g_c * L against the
+    threshold); on probe tiles the step change and the new gain are checked against fp64 sums over the
+    stored tensors, reused outputs against latent + residual, recomputed ones on sampled attention rows;
+    the blend on whole planes."""
+    g = CONFIGS["canvas4k_gate_bf16"]
+    n, steps = g.n_tiles, 6
+    E = int(np.prod(g.tile_shape))
+    qkv = _device_canvas(g)
+    x_a = []
+    for i in range(n):
+        tr, tc = divmod(i, g.n_tile_cols)
+        r0, c0 = tr * g.stride_h, tc * g.stride_w
+        x_a.append(torch.stack([t[:, :, r0:r0 + g.tile_h, c0:c0 + g.tile_w, :] for t in qkv]).contiguous())
+    del qkv
+    bufs = [x_a, [torch.empty_like(t) for t in x_a]]
+    outs = [[torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)]
+    delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)]
+    state = sg.GainState(n)
+    step_change = torch.empty(n, dtype=torch.float32, device="cuda")
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    rec = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    p = sg.make_problem(g)
+    gt = g.single_tile()
+    eps = eps_table(g.seed + 1000, steps, n)
+    thr = float(np.float32(g.threshold))
+    n_reused = 0
+    for k in range(steps):
+        cur, prev = bufs[k % 2], bufs[(k + 1) % 2]
+        if k:
+            for i in range(n):
+                cur[i].copy_(prev[i])
+                perturb_(cur[i], eps[k, i], g.seed + 100 * k + i)
+        o_cur, o_prev = outs[k % 2], outs[(k + 1) % 2]
+        gain_before = state.gain.cpu().numpy().copy()
+        len_before = state.path_len.cpu().numpy().copy()
+        known_before = state.has_gain.cpu().numpy().astype(bool)
+        sg.sg_denoise_step_gain(p, canvas, cur, prev, o_cur, o_prev, delta, state, g.threshold, step_change, scores,
+                                rec, ws)
+        torch.cuda.synchronize()
+        r = rec.cpu().numpy().astype(bool)
+        d, s = step_change.cpu().numpy(), scores.cpu().numpy()
+        gain_after, len_after = state.gain.cpu().numpy(), state.path_len.cpu().numpy()
+        print(f"step {k}: recompute={r.astype(int).tolist()}")
+        if k < 2:
+            assert r.all()                                     # the gain needs two outputs
+        for i in range(n):                                     # decisions follow from the stored state
+            L = np.float32(len_before[i] + d[i])
+            if known_before[i]:
+                sc = np.float32(gain_before[i] * L)
+                assert s[i] == sc and r[i] == (not (sc < np.float32(thr))), (k, i, s[i], sc)
+            else:
+                assert np.isinf(s[i]) and r[i]
+            assert len_after[i] == (np.float32(0.0) if r[i] else L)
+        probes = [(3 * k) % n, (7 * k + 11) % n] if k else []
+        for i in probes:
+            d_ref = _host_rel_l1(cur[i], prev[i])
+            assert abs(d[i] - d_ref) <= 2e-6 * max(1.0, d_ref), (k, i, d[i], d_ref)
+            if r[i]:
+                g_ref = _host_rel_l1(o_cur[i], o_prev[i]) / float(d[i])
+                assert abs(gain_after[i] - g_ref) <= 1e-5 * max(1.0, g_ref), (k, i, gain_after[i], g_ref)
+        for i in [j for j in range(n) if r[j]][:2]:            # recomputed: sampled attention rows, stored residual
+            x = cur[i]
+            _check_tile(gt, [x[0], x[1], x[2]], 0, 0, o_cur[i], [(5 * i + k) % g.heads], 8, g.seed + 31 * k + i)
+            sl = slice(12345, 12345 + 4096)
+            ref = to_f64(o_cur[i].reshape(-1)[sl]) - to_f64(x[0].reshape(-1)[sl])
+            assert float(np.abs(to_f64(delta[i][sl]) - ref).max()) <= 1e-6
+        for i in [j for j in range(n) if not r[j]][:2]:        # reused: latent + residual, one rounding
+            sl = slice(E - 4096, E)
+            ref = to_f64(cur[i][0].reshape(-1)[sl]) + to_f64(delta[i][sl])
+            got = to_f64(o_cur[i].reshape(-1)[sl])
+            assert float(np.abs(got - ref).max()) <= 2.0 ** -8 * max(1.0, float(np.abs(ref).max()))
+            n_reused += 1
+    assert state.has_prev.cpu().numpy().all() and state.has_gain.cpu().numpy().all()
+    assert n_reused > 0
+    _blend_plane_check(g, outs[(steps - 1) % 2], canvas, [(0, 0), (g.heads - 1, g.T - 1)])
