@@ -25,4 +25,7 @@ from .tile_oracle import (  # noqa: F401
     gain_gate,
     gain_refresh,
     denoise_step_gain,
+    tile_std,
+    StdTracker,
+    region_thresholds,
 )

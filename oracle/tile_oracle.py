@@ -339,3 +339,58 @@ def denoise_step_gain(tile_x, g, scale, state, thresholds, model=None, latent_of
         state.has_prev[i] = True
     canvas = blend(outs, g)
     return canvas, d, scores, recompute, outs
+
+
+# --------------------------------------------------------------------------
+# Intra-step region-aware cache control (Section 5.2; Appendix Algorithm 2):
+# an online tracker of the standard deviation of each tile's predicted noise,
+# and every Delta steps per-tile thresholds tau_i = tau_base * (1 + delta_i)
+# from the "MaxMin" or the "TopSelect" policy.
+#
+# Readings (the paper leaves them open): the tracker keeps, per tile, the
+# running mean over the steps seen so far of the population standard deviation
+# of that step's tile output; Normalized() is min-max scaling across tiles
+# (both policies only use the order of the normalised values, so any increasing
+# normalisation gives the same thresholds); ties go to the lowest tile index.
+# --------------------------------------------------------------------------
+def tile_std(x):
+    """Population standard deviation of all elements of one tile's output."""
+    a = np.asarray(x, dtype=np.float64).ravel()
+    return float(np.sqrt(np.mean((a - a.mean()) ** 2)))
+
+
+class StdTracker:
+    """StdTracker of Algorithm 2: running mean, per tile, of the per-step standard deviation."""
+
+    def __init__(self, n_tiles):
+        self.mean = np.zeros(n_tiles)
+        self.count = 0
+
+    def update(self, stds):
+        stds = np.asarray(stds, dtype=np.float64)
+        self.count += 1
+        self.mean = self.mean + (stds - self.mean) / self.count
+
+    def normalized(self):
+        lo, hi = self.mean.min(), self.mean.max()
+        return np.zeros_like(self.mean) if hi == lo else (self.mean - lo) / (hi - lo)
+
+
+def region_thresholds(sigma, tau_base, alpha, mode):
+    """tau_i = tau_base * (1 + delta_i) with delta = 0 except
+    "MaxMin":    delta[argmax sigma] = alpha, delta[argmin sigma] = -alpha / 2
+    "TopSelect": delta[largest] = alpha, delta[second largest] = alpha / 2
+    (argmin is applied after argmax, so with a single tile or all-equal values it wins)."""
+    sigma = np.asarray(sigma, dtype=np.float64)
+    delta = np.zeros(len(sigma))
+    if mode == "MaxMin":
+        delta[int(np.argmax(sigma))] = alpha
+        delta[int(np.argmin(sigma))] = -0.5 * alpha
+    elif mode == "TopSelect":
+        order = sorted(range(len(sigma)), key=lambda i: (-sigma[i], i))
+        delta[order[0]] = alpha
+        if len(order) > 1:
+            delta[order[1]] = 0.5 * alpha
+    else:
+        raise ValueError("mode must be 'MaxMin' or 'TopSelect'")
+    return float(tau_base) * (1.0 + delta)
