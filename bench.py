@@ -154,6 +154,10 @@ def full_extras(torch, sg, args):
     step_change = torch.full((n5,), 0.05, dtype=torch.float32, device="cuda")
     ms_r = time_calls(torch, lambda: sg.sg_gain_refresh(o_cur, o_prev, latent, delta, half, step_change, state, ws), 10)
     nb = float(E) * (10 * int(half.sum()) + 8 * (n5 - int(half.sum())))
+    tstd = torch.empty(n5, dtype=torch.float32, device="cuda")
+    ms_s = time_calls(torch, lambda: sg.sg_tile_std(o_cur, tstd, ws), 10)
+    res["tile_std_4k"] = {"ms": round(ms_s, 4), "GB/s": round(2.0 * E * n5 / ms_s * 1e-6, 1),
+                          "frac_hbm_peak": round(2.0 * E * n5 / ms_s * 1e-6 / PEAK_HBM_GBS, 4)}
     res["gain_refresh_4k"] = {"ms": round(ms_r, 4), "GB/s": round(nb / ms_r * 1e-6, 1),
                               "frac_hbm_peak": round(nb / ms_r * 1e-6 / PEAK_HBM_GBS, 4), "recomputed_tiles": int(half.sum())}
     return res

@@ -239,6 +239,37 @@ typedef struct sg_gain_step_io {
  * out_cur -> sg_gain_refresh -> Fuse of out_cur into grid_out.  Nothing is read back. */
 int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Intra-step region-aware cache control of the paper (Section 5.2; Appendix Algorithm 2): tiles
+ * whose predicted noise has a high standard deviation (slowly updating regions) get a larger
+ * threshold, so they skip more steps.  The paper leaves the tracker and the normalisation open;
+ * here the tracker is, per tile, the running mean over the steps seen of the population standard
+ * deviation of that step's tile output, Normalized() is min-max scaling across tiles (both
+ * policies use only the order of the normalised values), and ties go to the lowest tile index. */
+typedef enum { SG_REGION_MAXMIN = 0, SG_REGION_TOPSELECT = 1 } sg_region_mode;
+
+/* tile_std[i] = sqrt(mean(x_i^2) - mean(x_i)^2) over the elems_per_tile elements of tile i.
+ *   x          host array of n_tiles device pointers (16-byte aligned); elems_per_tile a multiple of 8
+ *   tile_std   device, n_tiles floats (out);  workspace: as sg_cache_gate */
+int sg_tile_std(const void* const* x, int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float* tile_std,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * StdTracker.Update with this step's tile_std, and, when `adjust` is non-zero (the caller sets it every
+ * Delta steps), tau_i = tau_base * (1 + delta_i) with delta = 0 except
+ *     SG_REGION_MAXMIN:    delta[argmax] = alpha, then delta[argmin] = -alpha/2
+ *     SG_REGION_TOPSELECT: delta[largest] = alpha, delta[second largest] = alpha/2
+ * over the tracked means.  The first call (track_count = 0) sets every threshold to tau_base if it
+ * does not adjust; other calls without `adjust` leave the thresholds as they are.
+ *   tile_std     device, n_tiles floats (in)
+ *   track_mean   device, n_tiles doubles (in/out);  track_count: device, one int32 (in/out, start at 0)
+ *   sigma        device, n_tiles floats (out, the normalised means; written only when adjusting) or NULL
+ *   thresholds   device, n_tiles floats (in/out): what sg_gain_gate takes as tile_thresholds
+ */
+int sg_region_thresholds(const float* tile_std, double* track_mean, int32_t* track_count, int32_t n_tiles,
+                         float tau_base, float alpha, int32_t mode, int32_t adjust, float* sigma,
+                         float* thresholds, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

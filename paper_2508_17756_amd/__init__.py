@@ -5,4 +5,5 @@ from .binding import (  # noqa: F401
     sg_version, sg_status_string, sg_problem_validate, sg_workspace_bytes,
     sg_tile_attention, sg_tile_blend, sg_cache_gate, sg_denoise_step_tiled,
     sg_gain_state, sg_gain_step_io, GainState, sg_gain_gate, sg_gain_refresh, sg_denoise_step_gain,
+    SG_REGION_MAXMIN, SG_REGION_TOPSELECT, sg_tile_std, sg_region_thresholds,
 )

@@ -10,6 +10,7 @@ import os
 
 SG_F32, SG_BF16 = 0, 1
 SG_OK, SG_ERR_INVALID_ARG, SG_ERR_UNSUPPORTED, SG_ERR_WORKSPACE, SG_ERR_HIP = 0, -1, -2, -3, -4
+SG_REGION_MAXMIN, SG_REGION_TOPSELECT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -104,6 +105,10 @@ def load_library():
                                     ctypes.c_size_t, vp]
     lib.sg_denoise_step_gain.restype = ctypes.c_int
     lib.sg_denoise_step_gain.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_gain_step_io), vp]
+    lib.sg_tile_std.restype = ctypes.c_int
+    lib.sg_tile_std.argtypes = [pp, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.sg_region_thresholds.restype = ctypes.c_int
+    lib.sg_region_thresholds.argtypes = [vp, vp, vp, i32, f32, f32, i32, i32, vp, vp, vp]
     _LIB = lib
     return lib
 
@@ -289,3 +294,23 @@ def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, 
     rc = load_library().sg_denoise_step_gain(ctypes.byref(p), ctypes.byref(io), _stream())
     _check(rc, "sg_denoise_step_gain")
     return grid_out
+
+
+def sg_tile_std(x, tile_std, workspace, elems_per_tile=None):
+    n = len(x)
+    elems = int(elems_per_tile if elems_per_tile is not None else (x[0].numel() if n else 8))
+    dt = _dtype_code(x[0]) if n else SG_BF16
+    rc = load_library().sg_tile_std(_ptr_array(x), n, elems, dt, _ptr(tile_std), _ptr(workspace), _nbytes(workspace),
+                                    _stream())
+    _check(rc, "sg_tile_std")
+    return tile_std
+
+
+def sg_region_thresholds(tile_std, track_mean, track_count, tau_base, alpha, mode, adjust, thresholds, sigma=None):
+    """track_mean: float64 device tensor, track_count: int32 device tensor of one element."""
+    n = int(tile_std.numel())
+    rc = load_library().sg_region_thresholds(_ptr(tile_std), _ptr(track_mean), _ptr(track_count), n, float(tau_base),
+                                             float(alpha), int(mode), int(bool(adjust)), _ptr(sigma), _ptr(thresholds),
+                                             _stream())
+    _check(rc, "sg_region_thresholds")
+    return thresholds

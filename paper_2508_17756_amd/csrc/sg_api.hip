@@ -263,4 +263,27 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
   return launch_blend(*p, (const void* const*)io->out_cur, io->grid_out, s);
 }
 
+int sg_tile_std(const void* const* x, int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float* tile_std,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_tiles < 0 || elems_per_tile <= 0 || (elems_per_tile & 7)) return SG_ERR_INVALID_ARG;
+  if (dtype != SG_F32 && dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (!tile_std || check_ptr_array(x, n_tiles) != SG_OK) return SG_ERR_INVALID_ARG;
+  if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  return launch_tile_std(x, n_tiles, elems_per_tile, dtype, tile_std, workspace, (hipStream_t)stream);
+}
+
+int sg_region_thresholds(const float* tile_std, double* track_mean, int32_t* track_count, int32_t n_tiles,
+                         float tau_base, float alpha, int32_t mode, int32_t adjust, float* sigma, float* thresholds,
+                         void* stream) {
+  if (n_tiles < 0) return SG_ERR_INVALID_ARG;
+  if (mode != SG_REGION_MAXMIN && mode != SG_REGION_TOPSELECT) return SG_ERR_INVALID_ARG;
+  if (std::isnan(tau_base) || std::isnan(alpha)) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (!tile_std || !track_mean || !track_count || !thresholds) return SG_ERR_INVALID_ARG;
+  return launch_region_thresholds(tile_std, track_mean, track_count, n_tiles, tau_base, alpha, mode, adjust != 0, sigma,
+                                  thresholds, (hipStream_t)stream);
+}
+
 }  // extern "C"

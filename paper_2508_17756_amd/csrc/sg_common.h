@@ -44,6 +44,10 @@ int launch_gain_gate(const void* const* x_cur, const void* const* x_prev, const 
 int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const void* const* latent,
                         float* const* delta, const uint8_t* recompute, const float* step_change,
                         const sg_gain_state& gs, int n_tiles, int64_t elems, int dtype, void* ws, hipStream_t s);
+int launch_tile_std(const void* const* x, int n_tiles, int64_t elems, int dtype, float* tile_std, void* ws, hipStream_t s);
+int launch_region_thresholds(const float* tile_std, double* track_mean, int32_t* track_count, int n_tiles,
+                             float tau_base, float alpha, int mode, int adjust, float* sigma, float* thresholds,
+                             hipStream_t s);
 int launch_cache_refresh(const void* const* src, void* const* dst, const uint8_t* recompute,
                          uint8_t* has_cache, int n_tiles, int64_t bytes_per_tile, hipStream_t s);
 
