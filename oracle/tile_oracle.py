@@ -394,3 +394,35 @@ def region_thresholds(sigma, tau_base, alpha, mode):
     else:
         raise ValueError("mode must be 'MaxMin' or 'TopSelect'")
     return float(tau_base) * (1.0 + delta)
+
+
+# --------------------------------------------------------------------------
+# Tile shifting (Algorithm 1 "ShiftThisStep" / "Shift"; Section 4.2: deterministic
+# shifts along both spatial directions with a fixed stride, which lets the tiles
+# stay non-overlapping).  The paper does not say what happens at the canvas edge;
+# the reading here keeps every tile whole and the canvas covered by wrapping
+# around: with shift (dy, dx) the token (i, j) of the tile with origin (r0, c0)
+# sits at canvas position ((r0 + i + dy) mod H, (c0 + j + dx) mod W).  That is the
+# unshifted partition applied to the canvas rolled by (-dy, -dx).
+# --------------------------------------------------------------------------
+def slice_tile_shifted(grid, g, tile_row, tile_col, shift_h, shift_w):
+    """SliceTile under a shifted partition: the unshifted window of the rolled canvas."""
+    rolled = np.roll(np.asarray(grid), shift=(-int(shift_h), -int(shift_w)), axis=(2, 3))
+    return slice_tile(rolled, g, tile_row, tile_col)
+
+
+def blend_shifted(tile_outs, g, shift_h, shift_w):
+    """Fuse under a shifted partition: the unshifted blend, rolled back by (dy, dx)."""
+    return np.roll(blend(tile_outs, g), shift=(int(shift_h), int(shift_w)), axis=(2, 3))
+
+
+# --------------------------------------------------------------------------
+# Scheduler update after Fuse (Algorithm 1: L <- Model.Denoise(L, n); Section 4.2:
+# the tile predictions are aggregated first so the whole canvas follows one
+# trajectory).  The paper does not fix the sampler; every first-order sampler step
+# (flow-matching Euler, DDIM) is affine in the latent and the fused prediction:
+#     L <- c_latent * L + c_noise * n .
+# --------------------------------------------------------------------------
+def fuse_and_denoise(tile_outs, g, latent, c_latent, c_noise, shift_h=0, shift_w=0):
+    n = blend_shifted(tile_outs, g, shift_h, shift_w)
+    return float(c_latent) * np.asarray(latent, dtype=np.float64) + float(c_noise) * n
