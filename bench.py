@@ -294,6 +294,11 @@ def main():
         canvas4 = torch.empty(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
         ms_blend = time_calls(torch, lambda: sg.sg_tile_blend(p4, tiles4, canvas4), 20)
         kernels["blend_4k"] = hbm(2.0 * (n4 * E4 + int(np.prod(g4.grid_shape))), ms_blend)
+        # Fuse + scheduler update in one pass: also reads the latent canvas, writes the new latent in place
+        lat4 = torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
+        ms_bu = time_calls(torch, lambda: sg.sg_tile_blend_update(p4, tiles4, lat4, 1.0, -0.02, lat4), 20)
+        kernels["blend_update_4k"] = hbm(2.0 * (n4 * E4 + 2 * int(np.prod(g4.grid_shape))), ms_bu)
+        del lat4
         # the 4K canvas step: 20 tile attentions read in place from the canvas tensors + blend
         q4, k4, v4 = (torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
         ms4 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4), 2, warmup=1)

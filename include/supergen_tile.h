@@ -71,6 +71,10 @@ typedef struct sg_problem {
   float scale;                      /* softmax scale applied to Q.K^T, > 0 (1/sqrt(head_dim))  */
   int64_t grid_stride_token;        /* canvas tensors: elements between consecutive tokens     */
   int64_t grid_stride_head;         /* canvas tensors: elements between consecutive heads      */
+  int32_t shift_h, shift_w;         /* tile shifting (Algorithm 1 "Shift"): offset of the whole partition on
+                                       the canvas, wrapping around: token (i, j) of tile (r, c) sits at canvas
+                                       row (r*stride_h + i + shift_h) mod H, column (c*stride_w + j + shift_w)
+                                       mod W.  0 <= shift_h < H, 0 <= shift_w < W; 0 = the fixed partition. */
 } sg_problem;
 
 /* Library version, "major.minor". */
@@ -96,7 +100,8 @@ int sg_workspace_bytes(int32_t n_tiles, size_t* out_bytes);
  *   q, k, v   device, canvas tensors (layout above); the tile is read in place, never copied
  *   out_tile  device, packed tile [heads][T][tile_h][tile_w][head_dim], 16-byte aligned
  * A packed tile is attended by describing it as a canvas that is one tile (H = tile_h,
- * W = tile_w, 1 x 1 tiles).
+ * W = tile_w, 1 x 1 tiles).  A shifted partition (shift_h or shift_w non-zero) is not read in
+ * place (SG_ERR_UNSUPPORTED): gather the tile with sg_tile_slice and attend the packed copy.
  */
 int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const void* v,
                       int32_t tile_row, int32_t tile_col, void* out_tile, void* stream);
@@ -108,11 +113,34 @@ int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const v
  *     w = w_h(i) * w_w(j),  w_axis(i) = min(1, (i+1)/(o+1), (L-i)/(o+1)),
  * i, j = the token's row/column inside the tile, L = tile length and o = L - stride along that
  * axis; the T axis carries weight 1.  With o = 0 this is the paper's non-overlapping placement.
+ * Under a shifted partition (shift_h, shift_w) tile tokens land at their wrapped canvas positions.
  * Weights and sums are fp32; one rounding to the output type.
  *   tile_out  host array of n_tile_rows*n_tile_cols device pointers to packed tiles (row-major)
  *   grid_out  device, canvas tensor with the problem's strides
  */
 int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_out, void* stream);
+
+/*
+ * Fuse followed by the scheduler update in one pass (Algorithm 1: n = Fuse(N); L = Model.Denoise(L, n);
+ * Section 4.2: the tile predictions are aggregated before the update so the canvas follows one
+ * trajectory).  Every first-order sampler step is affine in the latent and the fused prediction:
+ *     latent_out = c_latent * latent_in + c_noise * Fuse(tile_out)
+ * (flow-matching Euler: c_latent = 1, c_noise = sigma_next - sigma).  The fused prediction is never
+ * written to memory.  latent_in and latent_out are canvas tensors with the problem's strides;
+ * latent_out may be latent_in (update in place).  One rounding to the tensors' type.
+ */
+int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const void* latent_in, float c_latent,
+                         float c_noise, void* latent_out, void* stream);
+
+/*
+ * SliceTile into packed form (Algorithm 1 "SliceTile"; with shift_h / shift_w the shifted, wrapping
+ * partition of "Shift").  Gathers the window of tile (tile_row, tile_col) out of n_src (1..3) canvas
+ * tensors into dst = [n_src][heads][T][tile_h][tile_w][d]; with q, k, v as the sources dst is the
+ * packed tile input of sg_denoise_step_tiled's cached mode.
+ *   src   host array of n_src device pointers to canvas tensors;  dst: device, 16-byte aligned
+ */
+int sg_tile_slice(const sg_problem* p, const void* const* src, int32_t n_src, int32_t tile_row, int32_t tile_col,
+                  void* dst, void* stream);
 
 /*
  * Cache gate (Equation 3 relative L1 with the cached tensor as denominator; Equation 7:
@@ -156,7 +184,8 @@ typedef struct sg_step_io {
 /*
  * One stage-2 step over all tiles (Algorithm 1 loop body; Section 5.1: Tile Dispatcher ->
  * Threshold Comparator -> recompute or reuse -> Tile Fuser).
- *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.
+ *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  The
+ *     tiles are read in place, so the partition must not be shifted (SG_ERR_UNSUPPORTED otherwise).
  *   cached mode: gate every tile on tile_x[i] against cache_x[i]; for the tiles to recompute
  *     cache_out[i] = attention(tile_x[i]), cache_x[i] = tile_x[i], has_cache[i] = 1; reused
  *     tiles keep their cache entries untouched (drift stays measured from the last recomputed

@@ -30,7 +30,8 @@ class sg_problem(ctypes.Structure):
                 ("n_tile_rows", ctypes.c_int32), ("n_tile_cols", ctypes.c_int32),
                 ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("grid_stride_token", ctypes.c_int64), ("grid_stride_head", ctypes.c_int64)]
+                ("grid_stride_token", ctypes.c_int64), ("grid_stride_head", ctypes.c_int64),
+                ("shift_h", ctypes.c_int32), ("shift_w", ctypes.c_int32)]
 
 
 class sg_step_io(ctypes.Structure):
@@ -93,6 +94,10 @@ def load_library():
     lib.sg_tile_attention.argtypes = [ctypes.POINTER(sg_problem), vp, vp, vp, i32, i32, vp, vp]
     lib.sg_tile_blend.restype = ctypes.c_int
     lib.sg_tile_blend.argtypes = [ctypes.POINTER(sg_problem), pp, vp, vp]
+    lib.sg_tile_blend_update.restype = ctypes.c_int
+    lib.sg_tile_blend_update.argtypes = [ctypes.POINTER(sg_problem), pp, vp, f32, f32, vp, vp]
+    lib.sg_tile_slice.restype = ctypes.c_int
+    lib.sg_tile_slice.argtypes = [ctypes.POINTER(sg_problem), pp, i32, i32, i32, vp, vp]
     lib.sg_cache_gate.restype = ctypes.c_int
     lib.sg_cache_gate.argtypes = [pp, pp, vp, i32, i64, i32, f32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sg_denoise_step_tiled.restype = ctypes.c_int
@@ -144,7 +149,7 @@ def _check(status, where):
         raise SgError(status, where)
 
 
-def make_problem(geom, dtype=None, token_major=False):
+def make_problem(geom, dtype=None, token_major=False, shift=(0, 0)):
     """sg_problem for a geometry object with the fields of synthetic.TileGeometry (or any
     object with T, H, W, tile_h, tile_w, stride_h, stride_w, n_tile_rows, n_tile_cols, heads,
     head_dim, scale, dtype); canvas tensors are [heads][T][H][W][d] unless token_major."""
@@ -161,6 +166,7 @@ def make_problem(geom, dtype=None, token_major=False):
     else:
         p.grid_stride_token = p.head_dim
         p.grid_stride_head = p.T * p.H * p.W * p.head_dim
+    p.shift_h, p.shift_w = int(shift[0]), int(shift[1])
     return p
 
 
@@ -196,6 +202,21 @@ def sg_tile_blend(p, tile_out, grid_out):
     st = load_library().sg_tile_blend(ctypes.byref(p), arr, _ptr(grid_out), _stream())
     _check(st, "sg_tile_blend")
     return grid_out
+
+
+def sg_tile_blend_update(p, tile_out, latent_in, c_latent, c_noise, latent_out):
+    st = load_library().sg_tile_blend_update(ctypes.byref(p), _ptr_array(tile_out), _ptr(latent_in), float(c_latent),
+                                             float(c_noise), _ptr(latent_out), _stream())
+    _check(st, "sg_tile_blend_update")
+    return latent_out
+
+
+def sg_tile_slice(p, src, tile_row, tile_col, dst):
+    """src: list of 1..3 canvas tensors; dst: packed [len(src)][heads][T][tile_h][tile_w][d]."""
+    st = load_library().sg_tile_slice(ctypes.byref(p), _ptr_array(src), len(src), int(tile_row), int(tile_col),
+                                      _ptr(dst), _stream())
+    _check(st, "sg_tile_slice")
+    return dst
 
 
 def sg_cache_gate(x_cur, x_cached, has_cache, threshold, scores, recompute, workspace, elems_per_tile=None):

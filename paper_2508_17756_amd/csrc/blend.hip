@@ -16,7 +16,10 @@ struct BlendArgs {
   const void* tile[SG_MAX_TILES];
   int32_t T, H, W, th, tw, sh, sw, n_rows, n_cols, heads, d;
   int32_t vec_per_token_log2;  // log2(d / elements per 16-byte vector)
+  int32_t shift_h, shift_w;    // partition offset on the canvas, wrapping
   float inv_oh1, inv_ow1;      // 1/(o+1) per axis
+  float c_latent, c_noise;     // scheduler update: out = c_latent * latent + c_noise * fused
+  const void* latent;          // canvas tensor read by the update (may be the output itself)
   int64_t stride_token, stride_head;
   uint32_t plane_vecs;         // H*W*vec_per_token
 };
@@ -50,6 +53,21 @@ __device__ __forceinline__ u32x4 pack_vec(const float (&acc)[8], const float inv
   }
   return o;
 }
+// scheduler update on the fused value: c_latent * latent + c_noise * (acc * inv), one rounding
+template <int DT>
+__device__ __forceinline__ u32x4 pack_update(const float (&acc)[8], const float inv, const u32x4 lat, const float cl,
+                                             const float cn) {
+  u32x4 o;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (DT == SG_BF16)
+      o[c] = pack_bf16x2(cl * bf16_bits_to_f32(lat[c] & 0xffffu) + cn * (acc[2 * c] * inv),
+                         cl * __uint_as_float(lat[c] & 0xffff0000u) + cn * (acc[2 * c + 1] * inv));
+    else
+      o[c] = __float_as_uint(cl * __uint_as_float(lat[c]) + cn * (acc[c] * inv));
+  }
+  return o;
+}
 
 // A thread owns one 16-byte vector position (y, x, channel group) of the canvas plane and produces it for
 // kPlanes consecutive (head, frame) planes: the covering tiles, their weights and the reciprocal weight sum
@@ -58,14 +76,17 @@ __device__ __forceinline__ u32x4 pack_vec(const float (&acc)[8], const float inv
 // fixed register slot, absent ones carry weight 0 and are not loaded.
 constexpr int kPlanes = 2;
 
-template <int DT, int RC, int CC>
-__global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void* __restrict__ grid_out) {
+template <int DT, int RC, int CC, bool UPD>
+__global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void* grid_out) {
   constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
   const uint32_t v = blockIdx.x * kThreads + threadIdx.x;  // vector inside one (head, frame) plane
   if (v >= a.plane_vecs) return;
   const uint32_t token = v >> a.vec_per_token_log2;
   const int cv = v & ((1u << a.vec_per_token_log2) - 1);
-  const int y = token / (uint32_t)a.W, x = token - y * a.W;
+  const int yc = token / (uint32_t)a.W, xc = token - yc * a.W;   // canvas position written
+  // position in the unshifted partition (the partition sits at (shift_h, shift_w) on the canvas, wrapping)
+  int y = yc - a.shift_h; if (y < 0) y += a.H;
+  int x = xc - a.shift_w; if (x < 0) x += a.W;
 
   // tiles covering row y: tr*sh <= y < tr*sh + th, i.e. tr in [ceil((y-th+1)/sh), floor(y/sh)]
   int tr_hi = y / a.sh; if (tr_hi > a.n_rows - 1) tr_hi = a.n_rows - 1;
@@ -118,17 +139,22 @@ __global__ __launch_bounds__(kThreads) void blend_kernel(const BlendArgs a, void
     const int plane = plane0 + pl;  // head * T + t
     if (plane < n_planes) {
       const int head = plane / a.T, t = plane - head * a.T;
-      const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
+      const int64_t n = ((int64_t)t * a.H + yc) * a.W + xc;
       const int64_t off = (int64_t)head * a.stride_head + n * a.stride_token + (int64_t)cv * kPerVec;
       u32x4* dst = (u32x4*)((char*)grid_out + off * (DT == SG_BF16 ? 2 : 4));
-      __builtin_nontemporal_store(pack_vec<DT>(acc[pl], inv), dst);
+      if (UPD) {
+        const u32x4 lat = __builtin_nontemporal_load((const u32x4*)((const char*)a.latent + off * (DT == SG_BF16 ? 2 : 4)));
+        __builtin_nontemporal_store(pack_update<DT>(acc[pl], inv, lat, a.c_latent, a.c_noise), dst);
+      } else {
+        __builtin_nontemporal_store(pack_vec<DT>(acc[pl], inv), dst);
+      }
     }
   }
 }
 
 // Any coverage: the same computation with loops over the covering tiles, one plane per thread.
-template <int DT>
-__global__ __launch_bounds__(kThreads) void blend_any_kernel(const BlendArgs a, void* __restrict__ grid_out) {
+template <int DT, bool UPD>
+__global__ __launch_bounds__(kThreads) void blend_any_kernel(const BlendArgs a, void* grid_out) {
   constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
   const uint32_t v = blockIdx.x * kThreads + threadIdx.x;
   if (v >= a.plane_vecs) return;
@@ -136,7 +162,9 @@ __global__ __launch_bounds__(kThreads) void blend_any_kernel(const BlendArgs a, 
   const int head = plane / a.T, t = plane - head * a.T;
   const uint32_t token = v >> a.vec_per_token_log2;
   const int cv = v & ((1u << a.vec_per_token_log2) - 1);
-  const int y = token / (uint32_t)a.W, x = token - y * a.W;
+  const int yc = token / (uint32_t)a.W, xc = token - yc * a.W;
+  int y = yc - a.shift_h; if (y < 0) y += a.H;
+  int x = xc - a.shift_w; if (x < 0) x += a.W;
   int tr_hi = y / a.sh; if (tr_hi > a.n_rows - 1) tr_hi = a.n_rows - 1;
   int tr_lo = (y - a.th + a.sh) / a.sh; if (y - a.th + a.sh < 0) tr_lo = 0;
   int tc_hi = x / a.sw; if (tc_hi > a.n_cols - 1) tc_hi = a.n_cols - 1;
@@ -157,20 +185,67 @@ __global__ __launch_bounds__(kThreads) void blend_any_kernel(const BlendArgs a, 
       fma_vec<DT>(__builtin_nontemporal_load(src), w, acc);
     }
   }
-  const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
+  const int64_t n = ((int64_t)t * a.H + yc) * a.W + xc;
   const int64_t off = (int64_t)head * a.stride_head + n * a.stride_token + (int64_t)cv * kPerVec;
   u32x4* dst = (u32x4*)((char*)grid_out + off * (DT == SG_BF16 ? 2 : 4));
-  __builtin_nontemporal_store(pack_vec<DT>(acc, 1.0f / wsum), dst);
+  if (UPD) {
+    const u32x4 lat = __builtin_nontemporal_load((const u32x4*)((const char*)a.latent + off * (DT == SG_BF16 ? 2 : 4)));
+    __builtin_nontemporal_store(pack_update<DT>(acc, 1.0f / wsum, lat, a.c_latent, a.c_noise), dst);
+  } else {
+    __builtin_nontemporal_store(pack_vec<DT>(acc, 1.0f / wsum), dst);
+  }
+}
+
+// SliceTile under a (possibly shifted, wrapping) partition: gathers the window of tile (tile_row, tile_col)
+// out of up to three canvas tensors into one packed buffer [n_src][heads][T][tile_h][tile_w][d].  A plain
+// copy, one 16-byte vector per thread, the packed side fully coalesced.
+struct SliceArgs {
+  const void* src[3];
+  int32_t n_src, T, H, W, th, tw, r0, c0;     // r0, c0: canvas position of the tile's token (0, 0), before wrapping
+  int32_t vec_per_token_log2;
+  int64_t stride_token, stride_head;          // canvas strides in elements
+  int32_t elem_bytes;
+  uint32_t tile_plane_vecs;                   // th * tw * vectors per token
+  int32_t heads;
+};
+__global__ __launch_bounds__(kThreads) void slice_kernel(const SliceArgs a, u32x4* __restrict__ dst) {
+  const uint32_t v = blockIdx.x * kThreads + threadIdx.x;
+  if (v >= a.tile_plane_vecs) return;
+  const int plane = blockIdx.y;                 // head * T + t
+  const int which = blockIdx.z;
+  const int head = plane / a.T, t = plane - head * a.T;
+  const uint32_t token = v >> a.vec_per_token_log2;
+  const int cv = v & ((1u << a.vec_per_token_log2) - 1);
+  const int i = token / (uint32_t)a.tw, j = token - i * a.tw;
+  int y = a.r0 + i; if (y >= a.H) y -= a.H;
+  int x = a.c0 + j; if (x >= a.W) x -= a.W;
+  const int64_t n = ((int64_t)t * a.H + y) * a.W + x;
+  const int64_t off_bytes = ((int64_t)head * a.stride_head + n * a.stride_token) * a.elem_bytes + (int64_t)cv * 16;
+  const u32x4 val = __builtin_nontemporal_load((const u32x4*)((const char*)a.src[which] + off_bytes));
+  const int64_t planes = (int64_t)a.heads * a.T;
+  __builtin_nontemporal_store(val, dst + ((int64_t)which * planes + plane) * a.tile_plane_vecs + v);
 }
 
 }  // namespace
 
-int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, hipStream_t s) {
+template <int DT, bool UPD>
+static void launch_blend_cover(const BlendArgs& a, void* grid_out, int rc, int cc, dim3 grid_pl, dim3 grid_any, hipStream_t s) {
+  if (rc <= 1 && cc <= 1) blend_kernel<DT, 1, 1, UPD><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  else if (rc <= 2 && cc <= 2) blend_kernel<DT, 2, 2, UPD><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  else if (rc <= 3 && cc <= 3) blend_kernel<DT, 3, 3, UPD><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  else blend_any_kernel<DT, UPD><<<grid_any, kThreads, 0, s>>>(a, grid_out);
+}
+
+// latent == nullptr: plain Fuse; otherwise grid_out = c_latent * latent + c_noise * Fuse
+int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, const void* latent, float c_latent,
+                 float c_noise, hipStream_t s) {
   BlendArgs a;
   const int n_tiles = p.n_tile_rows * p.n_tile_cols;
   for (int i = 0; i < SG_MAX_TILES; ++i) a.tile[i] = i < n_tiles ? tile_out[i] : nullptr;
   a.T = p.T; a.H = p.H; a.W = p.W; a.th = p.tile_h; a.tw = p.tile_w; a.sh = p.stride_h; a.sw = p.stride_w;
   a.n_rows = p.n_tile_rows; a.n_cols = p.n_tile_cols; a.heads = p.heads; a.d = p.head_dim;
+  a.shift_h = p.shift_h; a.shift_w = p.shift_w;
+  a.latent = latent; a.c_latent = c_latent; a.c_noise = c_noise;
   const int per_vec = (p.dtype == SG_BF16) ? 8 : 4;
   const int vpt = p.head_dim / per_vec;
   int lg = 0; while ((1 << lg) < vpt) ++lg;
@@ -185,19 +260,32 @@ int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_ou
   const int rc = (p.tile_h + p.stride_h - 1) / p.stride_h, cc = (p.tile_w + p.stride_w - 1) / p.stride_w;
   const dim3 grid_pl(gx, (n_planes + kPlanes - 1) / kPlanes), grid_any(gx, n_planes);
   const bool bf = p.dtype == SG_BF16;
-  if (rc <= 1 && cc <= 1) {
-    if (bf) blend_kernel<SG_BF16, 1, 1><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
-    else blend_kernel<SG_F32, 1, 1><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
-  } else if (rc <= 2 && cc <= 2) {
-    if (bf) blend_kernel<SG_BF16, 2, 2><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
-    else blend_kernel<SG_F32, 2, 2><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
-  } else if (rc <= 3 && cc <= 3) {
-    if (bf) blend_kernel<SG_BF16, 3, 3><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
-    else blend_kernel<SG_F32, 3, 3><<<grid_pl, kThreads, 0, s>>>(a, grid_out);
+  if (latent) {
+    if (bf) launch_blend_cover<SG_BF16, true>(a, grid_out, rc, cc, grid_pl, grid_any, s);
+    else launch_blend_cover<SG_F32, true>(a, grid_out, rc, cc, grid_pl, grid_any, s);
   } else {
-    if (bf) blend_any_kernel<SG_BF16><<<grid_any, kThreads, 0, s>>>(a, grid_out);
-    else blend_any_kernel<SG_F32><<<grid_any, kThreads, 0, s>>>(a, grid_out);
+    if (bf) launch_blend_cover<SG_BF16, false>(a, grid_out, rc, cc, grid_pl, grid_any, s);
+    else launch_blend_cover<SG_F32, false>(a, grid_out, rc, cc, grid_pl, grid_any, s);
   }
+  SG_HIP_TRY(hipGetLastError());
+  return SG_OK;
+}
+
+int launch_slice(const sg_problem& p, const void* const* src, int n_src, int tile_row, int tile_col, void* dst,
+                 hipStream_t s) {
+  SliceArgs a;
+  for (int i = 0; i < 3; ++i) a.src[i] = i < n_src ? src[i] : nullptr;
+  a.n_src = n_src; a.T = p.T; a.H = p.H; a.W = p.W; a.th = p.tile_h; a.tw = p.tile_w; a.heads = p.heads;
+  a.r0 = (tile_row * p.stride_h + p.shift_h) % p.H;
+  a.c0 = (tile_col * p.stride_w + p.shift_w) % p.W;
+  a.elem_bytes = (p.dtype == SG_BF16) ? 2 : 4;
+  const int vpt = p.head_dim * a.elem_bytes / 16;
+  int lg = 0; while ((1 << lg) < vpt) ++lg;
+  a.vec_per_token_log2 = lg;
+  a.stride_token = p.grid_stride_token; a.stride_head = p.grid_stride_head;
+  a.tile_plane_vecs = (uint32_t)((int64_t)p.tile_h * p.tile_w * vpt);
+  dim3 grid((a.tile_plane_vecs + kThreads - 1) / kThreads, p.heads * p.T, n_src);
+  slice_kernel<<<grid, kThreads, 0, s>>>(a, (u32x4*)dst);
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }

@@ -36,6 +36,7 @@ static int validate(const sg_problem* p) {
                        ((int64_t)p->T * p->H * p->W - 1) * p->grid_stride_token + p->head_dim;
   if (span >= (1ll << 35)) return SG_ERR_UNSUPPORTED;
   if ((int64_t)p->H * p->W * (p->head_dim / 4) >= (1ll << 32)) return SG_ERR_UNSUPPORTED;
+  if (p->shift_h < 0 || p->shift_h >= p->H || p->shift_w < 0 || p->shift_w >= p->W) return SG_ERR_INVALID_ARG;
   return SG_OK;
 }
 
@@ -51,6 +52,7 @@ static TileView make_view(const sg_problem& p, int tile_row, int tile_col) {
 
 static int attention_dispatch(const sg_problem& p, const TileView& tv, const void* q, const void* k, const void* v,
                               void* out, const uint8_t* run_flag, hipStream_t s) {
+  if (p.shift_h != 0 || p.shift_w != 0) return SG_ERR_UNSUPPORTED;   // wrapped windows are gathered first (sg_tile_slice)
   if (p.dtype == SG_F32)
     return launch_attention_f32(tv, p.heads, p.head_dim, p.scale, (const float*)q, (const float*)k, (const float*)v,
                                 (float*)out, run_flag, s);
@@ -104,7 +106,31 @@ int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_o
   const int n_tiles = p->n_tile_rows * p->n_tile_cols;
   for (int i = 0; i < n_tiles; ++i)
     if (!tile_out[i] || !aligned16(tile_out[i])) return SG_ERR_INVALID_ARG;
-  return launch_blend(*p, tile_out, grid_out, (hipStream_t)stream);
+  return launch_blend(*p, tile_out, grid_out, nullptr, 0.f, 0.f, (hipStream_t)stream);
+}
+
+int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const void* latent_in, float c_latent,
+                         float c_noise, void* latent_out, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!tile_out || !latent_in || !latent_out || !aligned16(latent_in) || !aligned16(latent_out)) return SG_ERR_INVALID_ARG;
+  if (std::isnan(c_latent) || std::isnan(c_noise)) return SG_ERR_INVALID_ARG;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
+  for (int i = 0; i < n_tiles; ++i)
+    if (!tile_out[i] || !aligned16(tile_out[i])) return SG_ERR_INVALID_ARG;
+  return launch_blend(*p, tile_out, latent_out, latent_in, c_latent, c_noise, (hipStream_t)stream);
+}
+
+int sg_tile_slice(const sg_problem* p, const void* const* src, int32_t n_src, int32_t tile_row, int32_t tile_col,
+                  void* dst, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!src || n_src < 1 || n_src > 3 || !dst || !aligned16(dst)) return SG_ERR_INVALID_ARG;
+  for (int i = 0; i < n_src; ++i)
+    if (!src[i] || !aligned16(src[i])) return SG_ERR_INVALID_ARG;
+  if (tile_row < 0 || tile_row >= p->n_tile_rows || tile_col < 0 || tile_col >= p->n_tile_cols)
+    return SG_ERR_INVALID_ARG;
+  return launch_slice(*p, src, n_src, tile_row, tile_col, dst, (hipStream_t)stream);
 }
 
 int sg_cache_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache, int32_t n_tiles,
@@ -145,7 +171,7 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
                                 io->cache_out[tr * p->n_tile_cols + tc], nullptr, s);
         if (st != SG_OK) return st;
       }
-    return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, s);
+    return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);
   }
 
   // cached mode
@@ -165,6 +191,7 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   // a packed tile is a canvas that is exactly one tile
   sg_problem tp = *p;
   tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+  tp.shift_h = tp.shift_w = 0;
   tp.grid_stride_token = p->head_dim;
   tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
   const TileView tv = make_view(tp, 0, 0);
@@ -177,7 +204,7 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   st = launch_cache_refresh(io->tile_x, io->cache_x, io->recompute, io->has_cache, n_tiles,
                             3 * tile_elems * (int64_t)esz, s);
   if (st != SG_OK) return st;
-  return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, s);
+  return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);
 }
 
 static int check_gain_state(const sg_gain_state* st) {
@@ -247,6 +274,7 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
   if (st != SG_OK) return st;
   sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
   tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+  tp.shift_h = tp.shift_w = 0;
   tp.grid_stride_token = p->head_dim;
   tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
   const TileView tv = make_view(tp, 0, 0);
@@ -260,7 +288,7 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
   st = launch_gain_refresh(io->out_cur, io->out_prev, io->latent ? io->latent : io->tile_x, io->delta, io->recompute,
                            io->step_change, io->state, n_tiles, tile_elems, p->dtype, io->workspace, s);
   if (st != SG_OK) return st;
-  return launch_blend(*p, (const void* const*)io->out_cur, io->grid_out, s);
+  return launch_blend(*p, (const void* const*)io->out_cur, io->grid_out, nullptr, 0.f, 0.f, s);
 }
 
 int sg_tile_std(const void* const* x, int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float* tile_std,

@@ -34,7 +34,10 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
 int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const void* q,
                                   const void* k, const void* v, void* out, const uint8_t* run_flag,
                                   hipStream_t s);
-int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, hipStream_t s);
+int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, const void* latent, float c_latent,
+                 float c_noise, hipStream_t s);
+int launch_slice(const sg_problem& p, const void* const* src, int n_src, int tile_row, int tile_col, void* dst,
+                 hipStream_t s);
 int launch_gate(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache,
                 int n_tiles, int64_t elems, int dtype, float threshold, float* scores,
                 uint8_t* recompute, void* ws, hipStream_t s);

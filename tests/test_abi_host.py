@@ -22,8 +22,8 @@ def test_library_exports_every_declared_symbol(repo_root):
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(sg.sg_problem) == 13 * 4 + 4 + 16      # 13 int32/float + padding + 2 int64
-    assert sg.sg_problem.grid_stride_token.offset == 56
+    assert ctypes.sizeof(sg.sg_problem) == 13 * 4 + 4 + 16 + 8  # 13 int32/float + padding + 2 int64 + 2 int32
+    assert sg.sg_problem.grid_stride_token.offset == 56 and sg.sg_problem.shift_h.offset == 72
 
 
 @pytest.mark.parametrize("name", list(CONFIGS))
@@ -37,6 +37,7 @@ def test_benchmark_configs_validate(name):
     ("dtype", 5, sg.SG_ERR_INVALID_ARG), ("scale", float("nan"), sg.SG_ERR_INVALID_ARG),
     ("scale", 0.0, sg.SG_ERR_INVALID_ARG), ("grid_stride_token", 60, sg.SG_ERR_INVALID_ARG),
     ("head_dim", 96, sg.SG_ERR_UNSUPPORTED),
+    ("shift_h", 16, sg.SG_ERR_INVALID_ARG), ("shift_w", -1, sg.SG_ERR_INVALID_ARG),
 ])
 def test_invalid_problems(field, value, status):
     p = sg.make_problem(CONFIGS["tiny_f32"])
@@ -73,3 +74,11 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_gain_refresh(arr, arr, arr, None, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_gain_refresh(arr, arr, arr, arr, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 16, None) == sg.SG_ERR_WORKSPACE
     assert lib.sg_denoise_step_gain(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG
+    # shifted partitions: gathered, not read in place
+    ps = sg.make_problem(CONFIGS["tiny_f32"], shift=(3, 5))
+    assert sg.sg_problem_validate(ps) == sg.SG_OK
+    assert lib.sg_tile_attention(ctypes.byref(ps), 16, 16, 16, 0, 0, 16, None) == sg.SG_ERR_UNSUPPORTED
+    assert lib.sg_tile_slice(ctypes.byref(ps), arr, 4, 0, 0, 256, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_slice(ctypes.byref(ps), arr, 2, 2, 0, 256, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, None, 1.0, 0.1, 256, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, 256, float("nan"), 0.1, 256, None) == sg.SG_ERR_INVALID_ARG

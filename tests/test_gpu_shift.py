@@ -1,0 +1,129 @@
+"""GPU parity of tile shifting (sg_tile_slice, shifted sg_tile_blend) and of the fused scheduler update
+(sg_tile_blend_update) against the oracle."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2508_17756_amd as sg
+from synthetic import CONFIGS, TileGeometry, randn_tensor, torch_dtype
+from gpu_util import to_f64, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _geom(name, T, H, W, th, tw, sh, sw, heads, d, dtype, seed):
+    nr = (H - th) // sh + 1 if th < H else 1
+    nc = (W - tw) // sw + 1 if tw < W else 1
+    return TileGeometry(name, T, H, W, th, tw, sh, sw, nr, nc, heads, d, dtype, seed)
+
+
+GEOMS = {
+    "paper_2x3": lambda dt, d: _geom("p", 2, 6, 12, 3, 4, 3, 4, 2, d, dt, 11),        # non-overlapping, as in the paper
+    "overlap_2x2": lambda dt, d: replace(CONFIGS["tiny_f32"], dtype=dt, head_dim=d),
+    "triple_3x2": lambda dt, d: _geom("t", 2, 9, 7, 5, 4, 2, 3, 3, d, dt, 12),
+    "cover_5x4": lambda dt, d: _geom("c", 1, 15, 13, 9, 7, 2, 2, 3, d, dt, 13),
+}
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shift", [(0, 0), (1, 0), (0, 3), (2, 5), (5, 11)])
+@pytest.mark.parametrize("token_major", [False, True])
+def test_slice_is_the_wrapped_window(dtype, shift, token_major):
+    d = 64 if dtype == "f32" else 128
+    g = GEOMS["paper_2x3"](dtype, d)
+    canv = [randn_tensor(g.grid_shape, dtype, 20 + s).cuda() for s in range(3)]
+    p = sg.make_problem(g, token_major=token_major, shift=shift)
+    dev = [t.permute(1, 2, 3, 0, 4).contiguous() for t in canv] if token_major else canv
+    for n_src in (1, 3):
+        for tr, tc in ((0, 0), (1, 2), (1, 0)):
+            dst = torch.full((n_src,) + g.tile_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+            sg.sg_tile_slice(p, dev[:n_src], tr, tc, dst)
+            for s in range(n_src):
+                ref = oracle.slice_tile_shifted(to_f64(canv[s]), g, tr, tc, *shift)
+                assert np.array_equal(to_f64(dst[s]), ref), (n_src, tr, tc, s)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", list(GEOMS))
+@pytest.mark.parametrize("shift", [(0, 0), (1, 2), (4, 6)])
+def test_shifted_blend_and_fused_update(dtype, shape, shift):
+    d = 64 if dtype == "f32" else 128
+    g = GEOMS[shape](dtype, d)
+    tiles = [randn_tensor(g.tile_shape, dtype, 600 + i).cuda() for i in range(g.n_tiles)]
+    p = sg.make_problem(g, shift=shift)
+    out = torch.full(g.grid_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    sg.sg_tile_blend(p, tiles, out)
+    ref = oracle.blend_shifted([to_f64(t) for t in tiles], g, *shift)
+    assert_close(to_f64(out), ref, dtype, f"{shape} {shift}")
+    # scheduler update fused behind the blend: out of place, then in place
+    lat = randn_tensor(g.grid_shape, dtype, 77).cuda()
+    ref_u = oracle.fuse_and_denoise([to_f64(t) for t in tiles], g, to_f64(lat), 0.875, -0.05, *shift)
+    new = torch.full(g.grid_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    sg.sg_tile_blend_update(p, tiles, lat, 0.875, -0.05, new)
+    assert_close(to_f64(new), ref_u, dtype, f"update {shape} {shift}")
+    inplace = lat.clone()
+    sg.sg_tile_blend_update(p, tiles, inplace, 0.875, -0.05, inplace)
+    assert torch.equal(inplace, new)
+    # c_latent = 1, c_noise = 0 leaves the latent bit for bit; c_latent = 0, c_noise = 1 is the plain blend
+    keep = lat.clone()
+    sg.sg_tile_blend_update(p, tiles, keep, 1.0, 0.0, keep)
+    assert torch.equal(keep, lat)
+    sg.sg_tile_blend_update(p, tiles, lat, 0.0, 1.0, new)
+    assert torch.equal(new, out)
+
+
+@pytest.mark.parametrize("shift", [(0, 0), (2, 7), (5, 11)])
+def test_slice_then_blend_is_the_identity_for_non_overlapping_tiles(shift):
+    g = GEOMS["paper_2x3"]("bf16", 128)
+    c = randn_tensor(g.grid_shape, "bf16", 5).cuda()
+    p = sg.make_problem(g, shift=shift)
+    tiles = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            t = torch.empty((1,) + g.tile_shape, dtype=torch.bfloat16, device="cuda")
+            sg.sg_tile_slice(p, [c], tr, tc, t)
+            tiles.append(t[0])
+    out = torch.empty_like(c)
+    sg.sg_tile_blend(p, tiles, out)
+    assert torch.equal(out, c)
+
+
+def test_shifted_step_bf16():
+    """One stage-2 step under a shifted partition: gather every tile's Q, K, V, attend the packed tiles,
+    fuse at the shifted positions and apply the scheduler update — against the oracle end to end."""
+    g = _geom("sh", 2, 16, 24, 8, 12, 8, 12, 2, 128, "bf16", 31)         # 2 x 2 non-overlapping tiles, N = 192
+    shift = (3, 7)
+    p = sg.make_problem(g, shift=shift)
+    qkv = [randn_tensor(g.grid_shape, "bf16", g.seed + 7 * s).cuda() for s in range(3)]
+    n = g.n_tiles
+    tile_x = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            t = torch.empty((3,) + g.tile_shape, dtype=torch.bfloat16, device="cuda")
+            sg.sg_tile_slice(p, qkv, tr, tc, t)
+            tile_x.append(t)
+    cache_x = [torch.zeros_like(t) for t in tile_x]
+    cache_out = [torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    has_cache = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    rec = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    noise = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    sg.sg_denoise_step_tiled(p, noise, cache_out, tile_x=tile_x, cache_x=cache_x, has_cache=has_cache, threshold=0.05,
+                             scores=scores, recompute=rec, workspace=ws)
+    latent = randn_tensor(g.grid_shape, "bf16", 99).cuda()
+    new_latent = torch.empty_like(latent)
+    sg.sg_tile_blend_update(p, cache_out, latent, 1.0, -0.25, new_latent)
+    torch.cuda.synchronize()
+    outs = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            Q, K, V = (oracle.slice_tile_shifted(to_f64(t), g, tr, tc, *shift) for t in qkv)
+            o = np.stack([oracle.attention(Q[a].reshape(-1, 128), K[a].reshape(-1, 128), V[a].reshape(-1, 128), g.scale)
+                          for a in range(g.heads)]).reshape(g.tile_shape)
+            outs.append(o)
+    assert_close(to_f64(noise), oracle.blend_shifted(outs, g, *shift), "bf16", "fused noise")
+    assert_close(to_f64(new_latent), oracle.fuse_and_denoise(outs, g, to_f64(latent), 1.0, -0.25, *shift), "bf16", "latent")
