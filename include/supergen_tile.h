@@ -177,15 +177,19 @@ typedef struct sg_step_io {
   float* scores;          /* cached mode: device, n_tiles floats (out)                                          */
   uint8_t* recompute;     /* cached mode: device, n_tiles bytes (out)                                           */
   void* grid_out;         /* device, canvas tensor (out)                                                        */
-  void* workspace;        /* cached mode: device scratch, sg_workspace_bytes(n_tiles)                           */
+  void* workspace;        /* cached mode: device scratch, sg_workspace_bytes(n_tiles); canvas mode: optional,   */
+                          /* room for one packed tile input (see sg_denoise_step_tiled)                         */
   size_t workspace_bytes;
 } sg_step_io;
 
 /*
  * One stage-2 step over all tiles (Algorithm 1 loop body; Section 5.1: Tile Dispatcher ->
  * Threshold Comparator -> recompute or reuse -> Tile Fuser).
- *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  The
- *     tiles are read in place, so the partition must not be shifted (SG_ERR_UNSUPPORTED otherwise).
+ *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  If
+ *     `workspace` (256-byte aligned) holds at least one packed tile input, 3 * heads * T * tile_h *
+ *     tile_w * head_dim elements, every tile is gathered into it (sg_tile_slice) and attended in
+ *     packed form, which is faster than reading the canvas in place and is the only way under a
+ *     shifted partition (SG_ERR_UNSUPPORTED without a workspace, SG_ERR_WORKSPACE with a small one).
  *   cached mode: gate every tile on tile_x[i] against cache_x[i]; for the tiles to recompute
  *     cache_out[i] = attention(tile_x[i]), cache_x[i] = tile_x[i], has_cache[i] = 1; reused
  *     tiles keep their cache entries untouched (drift stays measured from the last recomputed

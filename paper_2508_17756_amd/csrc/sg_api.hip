@@ -165,10 +165,30 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   if (!io->tile_x) {  // canvas mode: every tile is recomputed from the shared canvas tensors
     if (!io->q || !io->k || !io->v) return SG_ERR_INVALID_ARG;
     if (!aligned16(io->q) || !aligned16(io->k) || !aligned16(io->v)) return SG_ERR_INVALID_ARG;
+    // With room for one packed tile input in the workspace every tile is gathered first (one plain copy) and
+    // attended in packed form: the packed loader is the fastest one, and wrapped (shifted) windows can only
+    // be read this way.  Without it the tiles are read in place.
+    const size_t packed_bytes = 3 * (size_t)tile_elems * esz;
+    const bool gather = io->workspace && !(((uintptr_t)io->workspace) & 255u) && io->workspace_bytes >= packed_bytes;
+    if (!gather && (p->shift_h != 0 || p->shift_w != 0)) return io->workspace ? SG_ERR_WORKSPACE : SG_ERR_UNSUPPORTED;
+    sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
+    tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+    tp.shift_h = tp.shift_w = 0;
+    tp.grid_stride_token = p->head_dim;
+    tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
+    const TileView packed_view = make_view(tp, 0, 0);
+    const void* src[3] = {io->q, io->k, io->v};
     for (int tr = 0; tr < p->n_tile_rows; ++tr)
       for (int tc = 0; tc < p->n_tile_cols; ++tc) {
-        st = attention_dispatch(*p, make_view(*p, tr, tc), io->q, io->k, io->v,
-                                io->cache_out[tr * p->n_tile_cols + tc], nullptr, s);
+        void* out = io->cache_out[tr * p->n_tile_cols + tc];
+        if (gather) {
+          st = launch_slice(*p, src, 3, tr, tc, io->workspace, s);
+          if (st != SG_OK) return st;
+          const char* x = (const char*)io->workspace;
+          st = attention_dispatch(tp, packed_view, x, x + tile_elems * esz, x + 2 * tile_elems * esz, out, nullptr, s);
+        } else {
+          st = attention_dispatch(*p, make_view(*p, tr, tc), io->q, io->k, io->v, out, nullptr, s);
+        }
         if (st != SG_OK) return st;
       }
     return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);

@@ -127,3 +127,40 @@ def test_shifted_step_bf16():
             outs.append(o)
     assert_close(to_f64(noise), oracle.blend_shifted(outs, g, *shift), "bf16", "fused noise")
     assert_close(to_f64(new_latent), oracle.fuse_and_denoise(outs, g, to_f64(latent), 1.0, -0.25, *shift), "bf16", "latent")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shift", [(0, 0), (3, 5)])
+def test_canvas_step_gathers_tiles_when_given_a_workspace(dtype, shift):
+    """Canvas mode with room for one packed tile in the workspace: same numbers as reading in place (bit for
+    bit, the arithmetic is the same) and, under a shifted partition, the oracle's shifted step."""
+    d = 64 if dtype == "f32" else 128
+    g = _geom("cw", 2, 14, 20, 8, 12, 6, 8, 2, d, dtype, 41)              # 2 x 2 overlapping tiles
+    td = torch_dtype(dtype)
+    qkv = [randn_tensor(g.grid_shape, dtype, g.seed + 7 * s).cuda() for s in range(3)]
+    E = int(np.prod(g.tile_shape))
+    ws = torch.empty(3 * E * (2 if dtype == "bf16" else 4) + 256, dtype=torch.uint8, device="cuda")
+    p = sg.make_problem(g, shift=shift)
+    tiles = [torch.empty(g.tile_shape, dtype=td, device="cuda") for _ in range(g.n_tiles)]
+    canvas = torch.empty(g.grid_shape, dtype=td, device="cuda")
+    sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2], workspace=ws)
+    torch.cuda.synchronize()
+    outs = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            Q, K, V = (oracle.slice_tile_shifted(to_f64(t), g, tr, tc, *shift) for t in qkv)
+            outs.append(np.stack([oracle.attention(Q[a].reshape(-1, d), K[a].reshape(-1, d), V[a].reshape(-1, d), g.scale)
+                                  for a in range(g.heads)]).reshape(g.tile_shape))
+    assert_close(to_f64(canvas), oracle.blend_shifted(outs, g, *shift), dtype, "canvas")
+    if shift == (0, 0):
+        tiles2 = [torch.empty(g.tile_shape, dtype=td, device="cuda") for _ in range(g.n_tiles)]
+        canvas2 = torch.empty(g.grid_shape, dtype=td, device="cuda")
+        sg.sg_denoise_step_tiled(p, canvas2, tiles2, q=qkv[0], k=qkv[1], v=qkv[2])
+        assert torch.equal(canvas2, canvas) and all(torch.equal(a, b) for a, b in zip(tiles, tiles2))
+    else:
+        with pytest.raises(sg.SgError) as e:                              # wrapped windows need the workspace
+            sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2])
+        assert e.value.status == sg.SG_ERR_UNSUPPORTED
+        with pytest.raises(sg.SgError) as e:
+            sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2], workspace=ws[:1024])
+        assert e.value.status == sg.SG_ERR_WORKSPACE
