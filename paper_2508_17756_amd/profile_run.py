@@ -11,6 +11,9 @@ Sections (choose with --kernels, comma separated):
   attention  sg_tile_attention on the 75,600-token tile, 40 heads x 128, bf16
   blend      sg_tile_blend of the 4K canvas (20 tiles of 75,600 tokens -> 21 x 135 x 240)
   gate       sg_cache_gate over 4 tiles of packed Q,K,V (2.32 GB per tile and side)
+  update     sg_tile_blend_update of the 4K canvas (blend + scheduler update in place)
+  refresh    sg_gain_refresh over 8 tiles, every second one recomputed
+  std        sg_tile_std over 8 tile outputs
 Every section prints the bytes (or FLOP) the algorithm needs per launch, so a counter
 summary can be set beside it.  Inputs are synthetic N(0,1) values generated on the device.
 """
@@ -25,7 +28,7 @@ if ROOT not in sys.path:
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--kernels", default="copy,attention,blend,gate")
+    ap.add_argument("--kernels", default="copy,attention,blend,gate,update,refresh,std")
     ap.add_argument("--reps", type=int, default=3)
     args = ap.parse_args()
     todo = args.kernels.split(",")
@@ -76,6 +79,46 @@ def main():
         say("blend: %d launches, per launch %d bytes read (tile outputs) + %d bytes written (canvas)"
             % (args.reps, 2 * g.n_tiles * int(np.prod(g.tile_shape)), 2 * int(np.prod(g.grid_shape))))
         del tiles, canvas
+
+    if "update" in todo:
+        g = CONFIGS["canvas4k_bf16"]
+        p = sg.make_problem(g)
+        tiles = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
+        latent = torch.randn(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+        for _ in range(args.reps):
+            sg.sg_tile_blend_update(p, tiles, latent, 1.0, -0.02, latent)
+        torch.cuda.synchronize()
+        say("update: %d launches, per launch %d bytes read (tile outputs + latent) + %d bytes written (latent)"
+            % (args.reps, 2 * (g.n_tiles * int(np.prod(g.tile_shape)) + int(np.prod(g.grid_shape))),
+               2 * int(np.prod(g.grid_shape))))
+        del tiles, latent
+
+    if "refresh" in todo or "std" in todo:
+        g = CONFIGS["canvas4k_bf16"]
+        n, E = 8, int(np.prod(g.tile_shape))
+        o_cur = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        if "refresh" in todo:
+            o_prev = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            latent = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)]
+            state = sg.GainState(n)
+            state.has_prev.fill_(1)
+            half = torch.tensor([i % 2 for i in range(n)], dtype=torch.uint8, device="cuda")
+            step_change = torch.full((n,), 0.05, dtype=torch.float32, device="cuda")
+            for _ in range(args.reps):
+                sg.sg_gain_refresh(o_cur, o_prev, latent, delta, half, step_change, state, ws)
+            torch.cuda.synchronize()
+            say("refresh: %d launches over %d tiles (%d recomputed), per launch %d bytes read + %d bytes written"
+                % (args.reps, n, n // 2, E * (6 * (n // 2) + 6 * (n - n // 2)), E * (4 * (n // 2) + 2 * (n - n // 2))))
+            del o_prev, latent, delta
+        if "std" in todo:
+            out = torch.empty(n, dtype=torch.float32, device="cuda")
+            for _ in range(args.reps):
+                sg.sg_tile_std(o_cur, out, ws)
+            torch.cuda.synchronize()
+            say("std: %d launches over %d tiles, per launch %d bytes read" % (args.reps, n, 2 * E * n))
+        del o_cur
 
     if "gate" in todo:
         g = CONFIGS["canvas4k_bf16"]
