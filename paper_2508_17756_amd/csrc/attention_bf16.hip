@@ -358,17 +358,19 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, both);
   };
-  // Fragment reads run kPF MFMA steps ahead of their use; the first K fragments of a QK product are read
-  // during the last steps of the PV product before it, so the matrix pipe does not drain between the two.
-  // (Reading the first V^T fragments ahead, during the softmax, was measured 7 % slower and is not done.)
+  // Fragment reads run kPF MFMA steps ahead of their use; the K fragments of the first step of a QK product
+  // are read during the last step of the PV product before it, so the matrix pipe does not drain between
+  // the two.  (Two steps ahead is no faster and spills registers; reading the first V^T fragments ahead,
+  // during the softmax, was measured 7 % slower.)
   constexpr int kPF = 2;
-  bf16x8 kpre[kPF][2];    // K fragments of the first kPF QK steps, read during the PV tail
+  constexpr int kKPre = 1;
+  bf16x8 kpre[kKPre][2];  // K fragments of the first kKPre QK steps, read during the PV tail
   // S^T = K Q^T of the stage at LDS byte offset `off`: two independent accumulator chains
   auto qk = [&](int off, f32x16 (&s)[2], bool prefetched) {
     bf16x8 a[D / 16][2];
 #pragma unroll
     for (int kk = 0; kk < kPF; ++kk) {
-      if (prefetched) { a[kk][0] = kpre[kk][0]; a[kk][1] = kpre[kk][1]; }
+      if (prefetched && kk < kKPre) { a[kk][0] = kpre[kk][0]; a[kk][1] = kpre[kk][1]; }
       else { a[kk][0] = kfrag(kk, 0, off); a[kk][1] = kfrag(kk, 1, off); }
     }
 #pragma unroll
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     }
   };
   // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d); if a QK product follows
-  // (K stage at `k_off`), its first fragments are read in the last steps
+  // (K stage at `k_off`), its first fragments are read in the last step
   auto pv = [&](int off, const bf16x8 (&pp)[4], int k_off, bool k_follows) {
     bf16x8 a[16];
 #pragma unroll
@@ -396,8 +398,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
       if (i + 2 * kPF < 16) {
         a[i + 2 * kPF] = vfrag((i + 2 * kPF) >> 2, (i + 2 * kPF) & 3, off);
         a[i + 2 * kPF + 1] = vfrag((i + 2 * kPF + 1) >> 2, (i + 2 * kPF + 1) & 3, off);
-      } else if (k_follows) {
-        const int kk = (i + 2 * kPF - 16) / 2;
+      } else if (k_follows && (i + 2 * kPF - 16) / 2 >= kPF - kKPre) {
+        const int kk = (i + 2 * kPF - 16) / 2 - (kPF - kKPre);
         kpre[kk][0] = kfrag(kk, 0, k_off);
         kpre[kk][1] = kfrag(kk, 1, k_off);
       }
