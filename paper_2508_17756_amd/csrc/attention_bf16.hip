@@ -595,11 +595,15 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   const int per_xcd = (total + kXcd - 1) / kXcd;
   const float c_log2 = scale * 1.4426950408889634f;
   dim3 grid(per_xcd * kXcd);
-  static bool attr_set[3] = {false, false, false};
+  // the kernels need more dynamic LDS than the default limit; the attribute is set once per device and kernel
+  constexpr int kMaxDevices = 64;
+  static bool attr_set[kMaxDevices][3] = {};
+  int dev = 0;
+  SG_HIP_TRY(hipGetDevice(&dev));
   auto launch = [&](auto kern, int slot) -> int {
-    if (!attr_set[slot]) {
+    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot]) {
       SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-      attr_set[slot] = true;
+      if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot] = true;
     }
     kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
                                            (const u32x4*)v, (uint16_t*)out, run_flag);

@@ -47,6 +47,14 @@ def test_invalid_problems(field, value, status):
     assert sg.sg_problem_validate(p) == status
 
 
+def test_tile_count_limit():
+    from synthetic import TileGeometry
+    ok = TileGeometry("m", 1, 17, 17, 2, 2, 1, 1, 16, 16, 1, 64, "f32", 0)
+    assert sg.sg_problem_validate(sg.make_problem(ok)) == sg.SG_OK                      # 256 tiles
+    over = TileGeometry("m", 1, 18, 17, 2, 2, 1, 1, 17, 16, 1, 64, "f32", 0)
+    assert sg.sg_problem_validate(sg.make_problem(over)) == sg.SG_ERR_UNSUPPORTED       # 272 tiles
+
+
 def test_null_and_workspace_checks_need_no_gpu():
     lib = sg.load_library()
     p = sg.make_problem(CONFIGS["tiny_f32"])

@@ -129,6 +129,20 @@ def test_blend_small(dtype, shape):
         assert np.array_equal(to_f64(out)[:, :, 0:4, 0:3, :], to_f64(tiles[0]))
 
 
+def test_blend_and_step_at_the_maximum_tile_count():
+    """256 tiles (16 x 16 of 2 x 2 tokens, stride 1): the most the ABI carries per canvas."""
+    g = _geom("max", 1, 17, 17, 2, 2, 1, 1, 1, 64, "f32", 57)
+    assert g.n_tiles == 256
+    q, k, v = canvas_qkv(g)
+    tiles = [torch.empty(g.tile_shape, dtype=torch.float32, device="cuda") for _ in range(g.n_tiles)]
+    canvas = torch.empty(g.grid_shape, dtype=torch.float32, device="cuda")
+    sg.sg_denoise_step_tiled(sg.make_problem(g), canvas, tiles, q=q, k=k, v=v)
+    outs = [oracle_tile_attention_full(g, q, k, v, tr, tc) for tr in range(16) for tc in range(16)]
+    for i in (0, 17, 255):
+        assert_close(to_f64(tiles[i]), outs[i], "f32", f"tile {i}")
+    assert_close(to_f64(canvas), oracle.blend(outs, g), "f32")
+
+
 def test_blend_token_major_canvas():
     g = _geom("tm", 2, 9, 7, 5, 4, 2, 3, 3, 128, "bf16", 53)
     tiles = [randn_tensor(g.tile_shape, "bf16", 700 + i).cuda() for i in range(g.n_tiles)]
