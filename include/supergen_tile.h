@@ -303,6 +303,38 @@ int sg_region_thresholds(const float* tile_std, double* track_mean, int32_t* tra
                          float tau_base, float alpha, int32_t mode, int32_t adjust, float* sigma,
                          float* thresholds, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * One refinement step of stage 2 with everything the paper attaches to it, in one call and with
+ * nothing read back (Algorithm 1 loop body with the cache of Section 5 and Algorithm 2's control):
+ *     gate with per-tile thresholds -> attention of the tiles to recompute -> cache store update /
+ *     residual reuse -> [StdTracker.Update and, when region->adjust, new thresholds] ->
+ *     Fuse [-> scheduler update]
+ * io        as for sg_denoise_step_gain; with `region` the gate reads region->thresholds (the
+ *           values left by the previous call; on a tile's first two steps they are not consulted)
+ * region    NULL, or Algorithm 2's state: see sg_tile_std / sg_region_thresholds for the fields
+ * update    NULL: the fused prediction is written to io->grid_out.  Otherwise
+ *           latent_out = c_latent * latent_in + c_noise * Fuse (sg_tile_blend_update) and
+ *           io->grid_out is not used. */
+typedef struct sg_region_control {
+  double* track_mean;    /* device, n_tiles (in/out)                                    */
+  int32_t* track_count;  /* device, one int32 (in/out, start at 0)                      */
+  float* tile_std;       /* device, n_tiles (out): this step's standard deviations      */
+  float* thresholds;     /* device, n_tiles (in/out): tau_i                             */
+  float* sigma;          /* device, n_tiles (out when adjusting) or NULL                */
+  float tau_base, alpha;
+  int32_t mode;          /* sg_region_mode                                              */
+  int32_t adjust;        /* non-zero on the steps where s mod Delta = 0                 */
+} sg_region_control;
+
+typedef struct sg_scheduler_update {
+  const void* latent_in; /* device, canvas tensor                                       */
+  void* latent_out;      /* device, canvas tensor; may be latent_in                     */
+  float c_latent, c_noise;
+} sg_scheduler_update;
+
+int sg_refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
+                   const sg_scheduler_update* update, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,18 @@ class sg_gain_step_io(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
+class sg_region_control(ctypes.Structure):
+    _fields_ = [("track_mean", ctypes.c_void_p), ("track_count", ctypes.c_void_p), ("tile_std", ctypes.c_void_p),
+                ("thresholds", ctypes.c_void_p), ("sigma", ctypes.c_void_p),
+                ("tau_base", ctypes.c_float), ("alpha", ctypes.c_float),
+                ("mode", ctypes.c_int32), ("adjust", ctypes.c_int32)]
+
+
+class sg_scheduler_update(ctypes.Structure):
+    _fields_ = [("latent_in", ctypes.c_void_p), ("latent_out", ctypes.c_void_p),
+                ("c_latent", ctypes.c_float), ("c_noise", ctypes.c_float)]
+
+
 def library_path():
     return os.path.join(_PKG, "libsupergen_tile.so")
 
@@ -110,6 +122,9 @@ def load_library():
                                     ctypes.c_size_t, vp]
     lib.sg_denoise_step_gain.restype = ctypes.c_int
     lib.sg_denoise_step_gain.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_gain_step_io), vp]
+    lib.sg_refine_step.restype = ctypes.c_int
+    lib.sg_refine_step.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_gain_step_io),
+                                   ctypes.POINTER(sg_region_control), ctypes.POINTER(sg_scheduler_update), vp]
     lib.sg_tile_std.restype = ctypes.c_int
     lib.sg_tile_std.argtypes = [pp, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]
     lib.sg_region_thresholds.restype = ctypes.c_int
@@ -299,7 +314,9 @@ def sg_gain_refresh(out_cur, out_prev, latent, delta, recompute, step_change, st
 
 
 def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, state, threshold, step_change,
-                         scores, recompute, workspace, latent=None, tile_thresholds=None):
+                         scores, recompute, workspace, latent=None, tile_thresholds=None, region=None, update=None):
+    """region: dict(track_mean, track_count, tile_std, thresholds, tau_base, alpha, mode, adjust[, sigma]);
+    update: dict(latent_in, latent_out, c_latent, c_noise).  With either one the call goes to sg_refine_step."""
     io = sg_gain_step_io()
     keep = [_ptr_array(tile_x), _ptr_array(prev_x), _ptr_array(out_cur), _ptr_array(out_prev), _ptr_array(delta)]
     io.tile_x, io.prev_x, io.out_cur, io.out_prev, io.delta = keep
@@ -312,9 +329,25 @@ def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, 
     io.step_change, io.scores, io.recompute = _ptr(step_change), _ptr(scores), _ptr(recompute)
     io.grid_out = _ptr(grid_out)
     io.workspace, io.workspace_bytes = _ptr(workspace), _nbytes(workspace)
-    rc = load_library().sg_denoise_step_gain(ctypes.byref(p), ctypes.byref(io), _stream())
-    _check(rc, "sg_denoise_step_gain")
-    return grid_out
+    if region is None and update is None:
+        rc = load_library().sg_denoise_step_gain(ctypes.byref(p), ctypes.byref(io), _stream())
+        _check(rc, "sg_denoise_step_gain")
+        return grid_out
+    rg = up = None
+    if region is not None:
+        rg = sg_region_control()
+        rg.track_mean, rg.track_count = _ptr(region["track_mean"]), _ptr(region["track_count"])
+        rg.tile_std, rg.thresholds, rg.sigma = _ptr(region["tile_std"]), _ptr(region["thresholds"]), _ptr(region.get("sigma"))
+        rg.tau_base, rg.alpha = float(region["tau_base"]), float(region["alpha"])
+        rg.mode, rg.adjust = int(region["mode"]), int(bool(region["adjust"]))
+    if update is not None:
+        up = sg_scheduler_update()
+        up.latent_in, up.latent_out = _ptr(update["latent_in"]), _ptr(update["latent_out"])
+        up.c_latent, up.c_noise = float(update["c_latent"]), float(update["c_noise"])
+    rc = load_library().sg_refine_step(ctypes.byref(p), ctypes.byref(io), ctypes.byref(rg) if rg is not None else None,
+                                       ctypes.byref(up) if up is not None else None, _stream())
+    _check(rc, "sg_refine_step")
+    return update["latent_out"] if update is not None else grid_out
 
 
 def sg_tile_std(x, tile_std, workspace, elems_per_tile=None):

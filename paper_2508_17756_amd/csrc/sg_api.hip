@@ -270,10 +270,23 @@ int sg_gain_refresh(void* const* out_cur, const void* const* out_prev, const voi
                              dtype, workspace, (hipStream_t)stream);
 }
 
-int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* stream) {
+static int refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
+                       const sg_scheduler_update* update, void* stream) {
   int st = validate(p);
   if (st != SG_OK) return st;
-  if (!io || !io->grid_out || !aligned16(io->grid_out)) return SG_ERR_INVALID_ARG;
+  if (!io) return SG_ERR_INVALID_ARG;
+  if (update) {
+    if (!update->latent_in || !update->latent_out || !aligned16(update->latent_in) || !aligned16(update->latent_out))
+      return SG_ERR_INVALID_ARG;
+    if (std::isnan(update->c_latent) || std::isnan(update->c_noise)) return SG_ERR_INVALID_ARG;
+  } else if (!io->grid_out || !aligned16(io->grid_out)) {
+    return SG_ERR_INVALID_ARG;
+  }
+  if (region) {
+    if (!region->track_mean || !region->track_count || !region->tile_std || !region->thresholds) return SG_ERR_INVALID_ARG;
+    if (region->mode != SG_REGION_MAXMIN && region->mode != SG_REGION_TOPSELECT) return SG_ERR_INVALID_ARG;
+    if (std::isnan(region->tau_base) || std::isnan(region->alpha)) return SG_ERR_INVALID_ARG;
+  }
   const int n_tiles = p->n_tile_rows * p->n_tile_cols;
   if (check_gain_state(&io->state) != SG_OK || !io->step_change || !io->scores || !io->recompute)
     return SG_ERR_INVALID_ARG;
@@ -290,7 +303,8 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
   const int64_t tile_elems = (int64_t)p->heads * p->T * p->tile_h * p->tile_w * p->head_dim;
 
   st = launch_gain_gate(io->tile_x, io->prev_x, io->state, n_tiles, 3 * tile_elems, p->dtype, io->threshold,
-                        io->tile_thresholds, io->step_change, io->scores, io->recompute, io->workspace, s);
+                        region ? region->thresholds : io->tile_thresholds, io->step_change, io->scores, io->recompute,
+                        io->workspace, s);
   if (st != SG_OK) return st;
   sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
   tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
@@ -308,7 +322,26 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
   st = launch_gain_refresh(io->out_cur, io->out_prev, io->latent ? io->latent : io->tile_x, io->delta, io->recompute,
                            io->step_change, io->state, n_tiles, tile_elems, p->dtype, io->workspace, s);
   if (st != SG_OK) return st;
+  if (region) {   // StdTracker.Update on this step's outputs, thresholds for the next step
+    st = launch_tile_std((const void* const*)io->out_cur, n_tiles, tile_elems, p->dtype, region->tile_std, io->workspace, s);
+    if (st != SG_OK) return st;
+    st = launch_region_thresholds(region->tile_std, region->track_mean, region->track_count, n_tiles, region->tau_base,
+                                  region->alpha, region->mode, region->adjust != 0, region->sigma, region->thresholds, s);
+    if (st != SG_OK) return st;
+  }
+  if (update)
+    return launch_blend(*p, (const void* const*)io->out_cur, update->latent_out, update->latent_in, update->c_latent,
+                        update->c_noise, s);
   return launch_blend(*p, (const void* const*)io->out_cur, io->grid_out, nullptr, 0.f, 0.f, s);
+}
+
+int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* stream) {
+  return refine_step(p, io, nullptr, nullptr, stream);
+}
+
+int sg_refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
+                   const sg_scheduler_update* update, void* stream) {
+  return refine_step(p, io, region, update, stream);
 }
 
 int sg_tile_std(const void* const* x, int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float* tile_std,

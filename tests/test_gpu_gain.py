@@ -203,3 +203,66 @@ def test_step_gain_chain_bf16():
             ost.path_len[i] = float(L[i])
             ost.delta[i] = to_f64(delta[i]).reshape(g.tile_shape)
     assert seen_reuse >= 4 and seen_recompute_late >= 2
+
+
+def test_refine_step_equals_its_parts():
+    """sg_refine_step (gate with per-tile thresholds -> attention -> cache update -> std tracker and threshold
+    adjustment -> Fuse + scheduler update) against the same sequence made of the separately checked entry
+    points, bit for bit over six steps, thresholds adjusted every second step."""
+    g = _geom("refine", 2, 14, 20, 8, 12, 6, 8, 2, 128, "bf16", 93)
+    n, E = g.n_tiles, int(np.prod(g.tile_shape))
+    p = sg.make_problem(g)
+    pt = sg.make_problem(g.single_tile())
+
+    def fresh():
+        return dict(outs=[[torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)],
+                    delta=[torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)],
+                    state=sg.GainState(n),
+                    step_change=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    scores=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    rec=torch.zeros(n, dtype=torch.uint8, device="cuda"),
+                    ws=torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda"),
+                    track_mean=torch.zeros(n, dtype=torch.float64, device="cuda"),
+                    track_count=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                    tile_std=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    thr=torch.full((n,), 0.05, dtype=torch.float32, device="cuda"),
+                    latent=randn_tensor(g.grid_shape, "bf16", 777).cuda())
+
+    a, b = fresh(), fresh()
+    x = [[randn_tensor((3,) + g.tile_shape, "bf16", 950 + i).cuda() for i in range(n)], None]
+    x[1] = [torch.zeros_like(t) for t in x[0]]
+    eps = [None, [0.02] * 4, [0.002, 0.2, 0.002, 0.2], [0.004, 0.002, 0.2, 0.002], [0.002] * 4, [0.2, 0.002, 0.004, 0.002]]
+    for k in range(len(eps)):
+        cur, prev = x[k % 2], x[(k + 1) % 2]
+        if k:
+            for i in range(n):
+                cur[i].copy_(prev[i])
+                perturb_(cur[i], eps[k][i], 7000 + 10 * k + i)
+        adjust = (k + 1) % 2 == 0
+        coef = (1.0, -0.05 * (k + 1))
+        # (a) one call
+        sg.sg_denoise_step_gain(p, None, cur, prev, a["outs"][k % 2], a["outs"][(k + 1) % 2], a["delta"], a["state"], 0.05,
+                                a["step_change"], a["scores"], a["rec"], a["ws"],
+                                region=dict(track_mean=a["track_mean"], track_count=a["track_count"], tile_std=a["tile_std"],
+                                            thresholds=a["thr"], tau_base=0.05, alpha=0.4, mode=sg.SG_REGION_MAXMIN,
+                                            adjust=adjust),
+                                update=dict(latent_in=a["latent"], latent_out=a["latent"], c_latent=coef[0], c_noise=coef[1]))
+        # (b) the parts
+        o_cur, o_prev = b["outs"][k % 2], b["outs"][(k + 1) % 2]
+        sg.sg_gain_gate(cur, prev, b["state"], 0.05, b["step_change"], b["scores"], b["rec"], b["ws"], tile_thresholds=b["thr"])
+        for i in [j for j, r in enumerate(b["rec"].cpu().tolist()) if r]:
+            sg.sg_tile_attention(pt, cur[i][0], cur[i][1], cur[i][2], 0, 0, o_cur[i])
+        sg.sg_gain_refresh(o_cur, o_prev, [t[0] for t in cur], b["delta"], b["rec"], b["step_change"], b["state"], b["ws"])
+        sg.sg_tile_std(o_cur, b["tile_std"], b["ws"])
+        sg.sg_region_thresholds(b["tile_std"], b["track_mean"], b["track_count"], 0.05, 0.4, sg.SG_REGION_MAXMIN, adjust, b["thr"])
+        sg.sg_tile_blend_update(p, o_cur, b["latent"], coef[0], coef[1], b["latent"])
+        torch.cuda.synchronize()
+        for key in ("step_change", "scores", "rec", "tile_std", "thr", "track_mean", "track_count", "latent"):
+            assert torch.equal(a[key], b[key]), (k, key)
+        for key in ("has_prev", "has_gain", "gain", "path_len"):
+            assert torch.equal(getattr(a["state"], key), getattr(b["state"], key)), (k, key)
+        for ta, tb in zip(a["outs"][k % 2] + a["delta"], o_cur + b["delta"]):
+            assert torch.equal(ta, tb), k
+    thr = a["thr"].cpu().numpy()
+    np.testing.assert_allclose(sorted((thr / np.float32(0.05)).tolist()), [0.8, 1.0, 1.0, 1.4], rtol=1e-6)   # MaxMin
+    assert int(a["track_count"].item()) == len(eps)
