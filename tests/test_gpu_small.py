@@ -109,6 +109,28 @@ def test_attention_bf16_large_logits_and_constant_v():
     assert float((got.float() - 0.75).abs().max()) <= 0.75 * 2 ** -7
 
 
+@pytest.mark.parametrize("order", ["ascending", "descending", "spike"])
+def test_attention_bf16_softmax_reference_moves(order):
+    """Scores that keep growing along the key axis (the running reference must move again and again),
+    that start at their maximum, or that hold one huge outlier: same numbers as the two-pass oracle."""
+    g = _geom("adv", 2, 12, 16, 12, 16, 12, 16, 2, 128, "bf16", 43)       # N = 384 = 6 stages
+    q, k, v = canvas_qkv(g)
+    N = g.tile_tokens
+    u = torch.nn.functional.normalize(randn_tensor((128,), "f32", 5).cuda(), dim=0)
+    ramp = torch.linspace(0.0, 1.0, N, device="cuda")
+    if order == "descending":
+        ramp = ramp.flip(0)
+    if order == "spike":
+        ramp = torch.zeros(N, device="cuda")
+        ramp[N // 2 + 7] = 1.0
+    # q along u with length 30; keys get up to 40 u: logits (scale 1/sqrt(128)) span ~0 .. 106, i.e. 150 in log2
+    q = (q.float() * 0.3 + 30.0 * u).to(torch.bfloat16)
+    k = (k.float() * 0.3 + (40.0 * ramp).reshape(1, g.T, g.tile_h, g.tile_w, 1) * u).to(torch.bfloat16)
+    got = gpu_tile_attention(g, q, k, v, 0, 0)
+    assert torch.isfinite(got.float()).all()
+    assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, 0, 0), "bf16", order)
+
+
 # ------------------------------------------------------------------ blend
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", ["tiny2x2", "triple3x2", "placement", "cover5x4", "oddplanes", "single"])
