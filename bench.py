@@ -154,6 +154,38 @@ def full_extras(torch, sg, args):
     step_change = torch.full((n5,), 0.05, dtype=torch.float32, device="cuda")
     ms_r = time_calls(torch, lambda: sg.sg_gain_refresh(o_cur, o_prev, latent, delta, half, step_change, state, ws), 10)
     nb = float(E) * (10 * int(half.sum()) + 8 * (n5 - int(half.sum())))
+    # the same drift under the paper's policy (gain, path length, residual reuse) with region-aware thresholds
+    # (MaxMin, adjusted every 2 steps) and the scheduler update fused behind the blend: sg_refine_step
+    del o_prev, latent
+    xb = [[randn_tensor((3,) + g5.tile_shape, "bf16", g5.seed + i, device="cuda") for i in range(n5)], None]
+    xb[1] = [torch.empty_like(t) for t in xb[0]]
+    outs = [cache_out, [torch.zeros(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]]
+    st2 = sg.GainState(n5)
+    region = dict(track_mean=torch.zeros(n5, dtype=torch.float64, device="cuda"),
+                  track_count=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                  tile_std=torch.zeros(n5, dtype=torch.float32, device="cuda"),
+                  thresholds=torch.full((n5,), g5.threshold, dtype=torch.float32, device="cuda"),
+                  tau_base=g5.threshold, alpha=0.4, mode=sg.SG_REGION_MAXMIN, adjust=False)
+    per_step = []
+    for k in range(g5.steps):
+        cur, prev = xb[k % 2], xb[(k + 1) % 2]
+        if k:
+            for i in range(n5):
+                cur[i].copy_(prev[i])
+                perturb_(cur[i], eps[k, i], g5.seed + 100 * k + i)
+        region["adjust"] = (k + 1) % 2 == 0
+        torch.cuda.synchronize()
+        e0, e1 = _events(torch)
+        e0.record()
+        sg.sg_denoise_step_gain(p5, None, cur, prev, outs[k % 2], outs[(k + 1) % 2], delta, st2, g5.threshold, step_change,
+                                scores, rec, ws, region=region,
+                                update=dict(latent_in=canvas, latent_out=canvas, c_latent=1.0, c_noise=-0.02))
+        e1.record()
+        e1.synchronize()
+        per_step.append({"ms": round(e0.elapsed_time(e1), 2), "recomputed": int(rec.sum())})
+    res["refine_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1), "steps": per_step}
+    del xb, outs
+    o_cur = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
     tstd = torch.empty(n5, dtype=torch.float32, device="cuda")
     ms_s = time_calls(torch, lambda: sg.sg_tile_std(o_cur, tstd, ws), 10)
     res["tile_std_4k"] = {"ms": round(ms_s, 4), "GB/s": round(2.0 * E * n5 / ms_s * 1e-6, 1),

@@ -3,7 +3,7 @@
 // (Equation 7: score >= threshold recomputes).
 //
 // Pure HBM streaming: each input element is read once.  Stage 1 runs one workgroup per compute
-// unit; a thread sums |a-b| and |b| in fp32 over its 16-byte vectors, the workgroup adds its
+// unit; a thread sums |a-b| and |b| in fp32 over its 16-byte vectors, each wavefront adds its
 // threads in fp64 and stores one (num, den) pair per tile.  Stage 2 adds the pairs of a tile in
 // a fixed order in fp64, so the score is bit-reproducible run to run on a given device.
 #include "sg_common.h"
@@ -12,6 +12,7 @@ namespace sg {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;   // every wavefront owns one partial slot per tile
 constexpr int kFinalThreads = 128;
 constexpr int kTilesPerLaunch = 64;
 
@@ -53,12 +54,10 @@ __global__ __launch_bounds__(kThreads) void gate_partial_kernel(GatePtrs ptrs, c
   const int64_t per_blk = (n_vec + n_blk - 1) / n_blk;
   const int64_t v0 = (int64_t)blk * per_blk;
   const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
-  __shared__ double s_num[2][kThreads / 64], s_den[2][kThreads / 64];
-  int par = 0;   // LDS slot of the next workgroup reduction; alternates, so one barrier per reduction suffices
   for (int tile = 0; tile < n_tiles; ++tile) {
-    double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk) * 2;
+    double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk * kWavesPerBlock) * 2;
     if (!has_cache[tile0 + tile]) {  // no cached input: nothing to compare, buffers are not read
-      if (threadIdx.x == 0) { out[0] = 0.0; out[1] = 0.0; }
+      if ((threadIdx.x & 63) == 0) { out[2 * (threadIdx.x >> 6)] = 0.0; out[2 * (threadIdx.x >> 6) + 1] = 0.0; }
       continue;
     }
     const u32x4* __restrict__ a = (const u32x4*)ptrs.cur[tile];
@@ -92,21 +91,16 @@ __global__ __launch_bounds__(kThreads) void gate_partial_kernel(GatePtrs ptrs, c
         den += (double)fabsf(bf);
       }
     }
-    // fixed-order tree over the workgroup: wavefront shuffles, then one value per wavefront via LDS
+    // fixed-order tree over the wavefront
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
       num += __shfl_down(num, off, 64);
       den += __shfl_down(den, off, 64);
     }
-    if ((threadIdx.x & 63) == 0) { s_num[par][threadIdx.x >> 6] = num; s_den[par][threadIdx.x >> 6] = den; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double n = 0.0, d = 0.0;
-      for (int w = 0; w < kThreads / 64; ++w) { n += s_num[par][w]; d += s_den[par][w]; }
-      out[0] = n;
-      out[1] = d;
+    if ((threadIdx.x & 63) == 0) {   // one partial pair per wavefront: no workgroup barrier between tiles
+      out[2 * (threadIdx.x >> 6)] = num;
+      out[2 * (threadIdx.x >> 6) + 1] = den;
     }
-    par ^= 1;
   }
 }
 
@@ -266,10 +260,8 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
   const int64_t per_blk = (n_vec + n_blk - 1) / n_blk;
   const int64_t v0 = (int64_t)blk * per_blk;
   const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
-  __shared__ double s_num[2][kThreads / 64], s_den[2][kThreads / 64];
-  int par = 0;
   for (int tile = 0; tile < n_tiles; ++tile) {
-    double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk) * 2;
+    double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk * kWavesPerBlock) * 2;
     u32x4* __restrict__ oc = (u32x4*)ptrs.out_cur[tile];
     const u32x4* __restrict__ lat = (const u32x4*)ptrs.latent[tile];
     u32x4* __restrict__ dl = (u32x4*)ptrs.delta[tile];
@@ -295,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
         else d0 = __builtin_nontemporal_load(dl + i);
         __builtin_nontemporal_store(residual_apply<DT>(l, d0, d1), oc + i);
       }
-      if (threadIdx.x == 0) { out[0] = 0.0; out[1] = 0.0; }
+      if ((threadIdx.x & 63) == 0) { out[2 * (threadIdx.x >> 6)] = 0.0; out[2 * (threadIdx.x >> 6) + 1] = 0.0; }
       continue;
     }
     // recompute: store the residual; relative change of the output against the previous step's
@@ -337,15 +329,10 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
       num += __shfl_down(num, off, 64);
       den += __shfl_down(den, off, 64);
     }
-    if ((threadIdx.x & 63) == 0) { s_num[par][threadIdx.x >> 6] = num; s_den[par][threadIdx.x >> 6] = den; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double n = 0.0, d = 0.0;
-      for (int w = 0; w < kThreads / 64; ++w) { n += s_num[par][w]; d += s_den[par][w]; }
-      out[0] = n;
-      out[1] = d;
+    if ((threadIdx.x & 63) == 0) {   // one partial pair per wavefront: no workgroup barrier between tiles
+      out[2 * (threadIdx.x >> 6)] = num;
+      out[2 * (threadIdx.x >> 6) + 1] = den;
     }
-    par ^= 1;
   }
 }
 
@@ -399,8 +386,8 @@ static int launch_partials(const void* const* a, const void* const* b, const uin
   int dev = 0, n_cu = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots ? kGateSlots : n_cu);
-  *n_slots = n_blk;
+  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots / kWavesPerBlock ? kGateSlots / kWavesPerBlock : n_cu);
+  *n_slots = n_blk * kWavesPerBlock;
   for (int t0 = 0; t0 < n_tiles; t0 += kTilesPerLaunch) {
     const int n = (n_tiles - t0 < kTilesPerLaunch) ? n_tiles - t0 : kTilesPerLaunch;
     GatePtrs ptrs;
@@ -451,7 +438,7 @@ int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const
   SG_HIP_TRY(hipGetDevice(&dev));
   SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   int n_blk = (n_cu < 1 ? 1 : n_cu) * kRefreshBlocksPerCu;
-  if (n_blk > kGateSlots) n_blk = kGateSlots;
+  if (n_blk > kGateSlots / kWavesPerBlock) n_blk = kGateSlots / kWavesPerBlock;
   for (int t0 = 0; t0 < n_tiles; t0 += kRefreshTilesPerLaunch) {
     const int n = (n_tiles - t0 < kRefreshTilesPerLaunch) ? n_tiles - t0 : kRefreshTilesPerLaunch;
     GainPtrs ptrs;
@@ -467,7 +454,7 @@ int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const
       gain_refresh_kernel<SG_F32><<<n_blk, kThreads, 0, s>>>(ptrs, recompute, gs.has_prev, t0, n, elems, partial);
     SG_HIP_TRY(hipGetLastError());
   }
-  gain_refresh_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk, recompute, step_change, gs.has_prev,
+  gain_refresh_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk * kWavesPerBlock, recompute, step_change, gs.has_prev,
                                                                  gs.has_gain, gs.gain, gs.path_len);
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;

@@ -45,8 +45,6 @@ __global__ __launch_bounds__(kThreads) void tile_moments_kernel(StdPtrs ptrs, in
   const int64_t per_blk = (n_vec + n_blk - 1) / n_blk;
   const int64_t v0 = (int64_t)blk * per_blk;
   const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
-  __shared__ double s_a[2][kThreads / 64], s_b[2][kThreads / 64];
-  int par = 0;
   for (int tile = 0; tile < n_tiles; ++tile) {
     const u32x4* __restrict__ x = (const u32x4*)ptrs.x[tile];
     float pivot;
@@ -54,13 +52,15 @@ __global__ __launch_bounds__(kThreads) void tile_moments_kernel(StdPtrs ptrs, in
     else pivot = ((const float*)ptrs.x[tile])[0];
     float a0 = 0.f, b0 = 0.f, a1 = 0.f, b1 = 0.f;
     int64_t i = v0 + threadIdx.x;
-    for (; i + 3 * kThreads < v1; i += 4 * kThreads) {
-      const u32x4 x0 = __builtin_nontemporal_load(x + i), x1 = __builtin_nontemporal_load(x + i + kThreads);
-      const u32x4 x2 = __builtin_nontemporal_load(x + i + 2 * kThreads), x3 = __builtin_nontemporal_load(x + i + 3 * kThreads);
-      moments_vec<DT>(x0, pivot, a0, b0);
-      moments_vec<DT>(x1, pivot, a1, b1);
-      moments_vec<DT>(x2, pivot, a0, b0);
-      moments_vec<DT>(x3, pivot, a1, b1);
+    for (; i + 7 * kThreads < v1; i += 8 * kThreads) {   // eight 16-byte loads in flight per thread
+      u32x4 xv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) xv[u] = __builtin_nontemporal_load(x + i + u * kThreads);
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        moments_vec<DT>(xv[u], pivot, a0, b0);
+        moments_vec<DT>(xv[u + 1], pivot, a1, b1);
+      }
     }
     for (; i < v1; i += kThreads) moments_vec<DT>(__builtin_nontemporal_load(x + i), pivot, a0, b0);
     double s1 = (double)a0 + (double)a1, s2 = (double)b0 + (double)b1;
@@ -69,16 +69,12 @@ __global__ __launch_bounds__(kThreads) void tile_moments_kernel(StdPtrs ptrs, in
       s1 += __shfl_down(s1, off, 64);
       s2 += __shfl_down(s2, off, 64);
     }
-    if ((threadIdx.x & 63) == 0) { s_a[par][threadIdx.x >> 6] = s1; s_b[par][threadIdx.x >> 6] = s2; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double n = 0.0, d = 0.0;
-      for (int w = 0; w < kThreads / 64; ++w) { n += s_a[par][w]; d += s_b[par][w]; }
-      double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk) * 2;
-      out[0] = n;
-      out[1] = d;
+    // one partial pair per wavefront: no workgroup barrier between tiles
+    if ((threadIdx.x & 63) == 0) {
+      double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk * (kThreads / 64) + (threadIdx.x >> 6)) * 2;
+      out[0] = s1;
+      out[1] = s2;
     }
-    par ^= 1;
   }
 }
 
@@ -158,7 +154,8 @@ int launch_tile_std(const void* const* x, int n_tiles, int64_t elems, int dtype,
   int dev = 0, n_cu = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots ? kGateSlots : n_cu);
+  constexpr int kWavesPerBlock = kThreads / 64;   // one partial slot per wavefront
+  const int n_blk = n_cu < 1 ? 1 : (n_cu > kGateSlots / kWavesPerBlock ? kGateSlots / kWavesPerBlock : n_cu);
   for (int t0 = 0; t0 < n_tiles; t0 += kTilesPerLaunch) {
     const int n = (n_tiles - t0 < kTilesPerLaunch) ? n_tiles - t0 : kTilesPerLaunch;
     StdPtrs ptrs;
@@ -167,7 +164,7 @@ int launch_tile_std(const void* const* x, int n_tiles, int64_t elems, int dtype,
     else tile_moments_kernel<SG_F32><<<n_blk, kThreads, 0, s>>>(ptrs, t0, n, elems, partial);
     SG_HIP_TRY(hipGetLastError());
   }
-  tile_std_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk, elems, tile_std);
+  tile_std_finalize_kernel<<<n_tiles, kFinalThreads, 0, s>>>(partial, n_blk * kWavesPerBlock, elems, tile_std);
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }
