@@ -150,6 +150,7 @@ def test_step_gain_chain_bf16():
            [0.2, 0.002, 0.002, 0.002], [0.002, 0.002, 0.002, 0.2]]
     bufs = [x_a, x_b]
     ost = oracle.GainState(n)
+    ost_free = oracle.GainState(n)        # a second oracle chain that never sees a GPU value: its own attention engine
     seen_reuse = seen_recompute_late = 0
     for k in range(len(eps)):
         cur, prev = bufs[k % 2], bufs[(k + 1) % 2]
@@ -166,6 +167,11 @@ def test_step_gain_chain_bf16():
         ref_canvas, d_ref, s_ref, r_ref, ref_outs = oracle.denoise_step_gain(
             [tuple(to_f64(t[j]) for j in range(3)) for t in cur], g, g.scale, ost, [thr] * n,
             model=lambda i, Q, K, V: gpu_out[i], store=_bf16_round)
+        # ... and the free-running oracle chain: same decisions (the margins are wide), canvas within tolerance
+        free_canvas, _, s_free, r_free, _ = oracle.denoise_step_gain(
+            [tuple(to_f64(t[j]) for j in range(3)) for t in cur], g, g.scale, ost_free, [thr] * n, store=_bf16_round)
+        assert list(r) == list(r_free), (k, s_free)
+        assert_close(to_f64(canvas), free_canvas, "bf16", f"free-running oracle, step {k}")
         d, s = step_change.cpu().numpy(), scores.cpu().numpy()
         for i in range(n):
             assert _close(d[i], d_ref[i]), (k, i, d[i], d_ref[i])
