@@ -68,6 +68,36 @@ def _blend_plane_check(g, tiles, canvas, planes):
         assert ma <= BF16_MAX_ABS and rl <= BF16_REL_L2, (a, t, ma, rl)
 
 
+def _end_to_end_tokens(g, qkv, canvas, head, tokens):
+    """Canvas tokens against the oracle alone: fp64 attention rows of the token in every tile that covers
+    it, fused by the oracle's blend (tiles that are NaN everywhere else)."""
+    from dataclasses import replace
+    g1 = replace(g, heads=1, T=1)
+    kv_cache = {}
+    for (t, y, x) in tokens:
+        tiles = []
+        for tr in range(g.n_tile_rows):
+            for tc in range(g.n_tile_cols):
+                r0, c0 = tr * g.stride_h, tc * g.stride_w
+                o = np.full((1, 1, g.tile_h, g.tile_w, g.head_dim), np.nan)
+                if r0 <= y < r0 + g.tile_h and c0 <= x < c0 + g.tile_w:
+                    if (tr, tc) not in kv_cache:
+                        kv_cache[(tr, tc)] = [to_f64(z[head, :, r0:r0 + g.tile_h, c0:c0 + g.tile_w, :]).reshape(g.tile_tokens, g.head_dim)
+                                              for z in qkv]
+                    Q, K, V = kv_cache[(tr, tc)]
+                    i, j = y - r0, x - c0
+                    row = (t * g.tile_h + i) * g.tile_w + j
+                    o[0, 0, i, j, :] = oracle.attention_rows(Q[row:row + 1], K, V, g.scale)[0]
+                tiles.append(o)
+        ref = oracle.blend(tiles, g1)[0, 0, y, x, :]
+        got = to_f64(canvas[head, t, y, x, :])
+        assert np.isfinite(ref).all()
+        ma = float(np.abs(got - ref).max())
+        rl = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        assert ma <= BF16_MAX_ABS and rl <= 4 * BF16_REL_L2, (t, y, x, ma, rl)   # 128 values: the L2 bound is a statistic, allow slack
+        kv_cache = {k: v for k, v in kv_cache.items() if k in list(kv_cache)[-2:]}   # bound host memory
+
+
 @pytest.mark.parametrize("name,rows_per_tile", [("canvas2k_bf16", 32), ("canvas4k_bf16", 16)])
 def test_config3_and_4_tiled_step(name, rows_per_tile):
     g = CONFIGS[name]
@@ -80,6 +110,12 @@ def test_config3_and_4_tiled_step(name, rows_per_tile):
         tr, tc = divmod(i, g.n_tile_cols)
         _check_tile(g, qkv, tr, tc, tiles[i], [(7 * i + 3) % g.heads], rows_per_tile, g.seed + i)
     _blend_plane_check(g, tiles, canvas, [(0, 0), (g.heads - 1, g.T - 1), (17, 9)])
+    # end to end against the oracle alone: a corner (one tile), an edge of an overlap, the most covered
+    # region, the last token
+    oh, ow = g.tile_h - g.stride_h, g.tile_w - g.stride_w
+    toks = [(0, 0, 0), (g.T // 2, g.stride_h, g.stride_w + ow // 2), (g.T - 1, g.H - 1, g.W - 1)]
+    toks.append((3, 2 * g.stride_h + 1, g.stride_w + 1) if name == "canvas2k_bf16" else (3, g.stride_h + oh - 1, 2 * g.stride_w + 3))
+    _end_to_end_tokens(g, qkv, canvas, 17, toks)
 
 
 def test_config5_gated_steps():
