@@ -63,6 +63,20 @@ def counter_summary(name):
     return vals
 
 
+def achievable_peaks():
+    """Runs the stand-alone probe built next to the library (bare MFMA loop on zero and on N(0,1) operands,
+    plain HBM streams) and returns its figures, or None if it is not there."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2508_17756_amd", "peak_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        return json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
+    except Exception:
+        return None
+
+
 def build_tile_inputs(torch, g, n_tiles, seed):
     """Per-tile packed [3][heads][T][th][tw][d] inputs, N(0,1) bf16, generated on the device."""
     from synthetic import randn_tensor
@@ -347,6 +361,11 @@ def main():
         if args.full:
             kernels.update(full_extras(torch, sg, args))
         out["kernels"] = kernels
+        # measured achievable rates of this device, beside the vendor peaks the fractions are quoted against
+        peaks = achievable_peaks()
+        out["achievable_peaks"] = peaks
+        if peaks:
+            out["roofline"]["frac_of_measured_mfma_on_normal_data"] = round(att_tflops / peaks["mfma_bf16_normal_tflops"], 4)
         heads = sorted(set(np.linspace(0, gt.heads - 1, min(args.cpu_heads, gt.heads)).round().astype(int).tolist()))
         cb, rows, outs = cpu_baseline(torch, gt, x_a[0], args.cpu_rows if gt.tile_tokens > 10000 else 64, heads)
         out["cpu_baseline"] = cb

@@ -8,6 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsupergen_tile.so")
+PROBE = os.path.join(PKG, "peak_probe.bin")
 SOURCES = ["sg_api.hip", "attention_bf16.hip", "attention_bf16_generic.hip", "attention_f32.hip", "blend.hip",
            "gate.hip", "region.hip"]
 # per-file extras: the streaming attention kernel takes row maxima with three-operand max instructions,
@@ -42,6 +43,9 @@ def build(verbose=False):
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    # stand-alone probe of the device's achievable MFMA and HBM rates (bench.py sets it beside the vendor peaks)
+    _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          os.path.join(CSRC, "peak_probe.hip"), "-o", PROBE])
     return LIB
 
 
