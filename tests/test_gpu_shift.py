@@ -164,3 +164,41 @@ def test_canvas_step_gathers_tiles_when_given_a_workspace(dtype, shift):
         with pytest.raises(sg.SgError) as e:
             sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2], workspace=ws[:1024])
         assert e.value.status == sg.SG_ERR_WORKSPACE
+
+
+def _random_tilings(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        T = int(rng.integers(1, 4))
+        th, tw = int(rng.integers(1, 10)), int(rng.integers(1, 10))
+        sh, sw = int(rng.integers(1, th + 1)), int(rng.integers(1, tw + 1))
+        nr, nc = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        H, W = (nr - 1) * sh + th, (nc - 1) * sw + tw
+        heads = int(rng.integers(1, 4))
+        out.append((T, H, W, th, tw, sh, sw, nr, nc, heads, int(rng.integers(0, H)), int(rng.integers(0, W)),
+                    str(rng.choice(["f32", "bf16"]))))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_tilings(30, 77), ids=lambda c: "T%d_%dx%d_tile%dx%d_s%dx%d_%dx%d_h%d_shift%d_%d_%s" % c)
+def test_blend_slice_update_random_tilings(case):
+    """Seeded random tilings (coverage from 1 x 1 up to 9 x 9, odd plane counts, any shift): slice, blend and
+    fused update against the oracle."""
+    T, H, W, th, tw, sh, sw, nr, nc, heads, dy, dx, dtype = case
+    d = 64 if dtype == "f32" else 128
+    g = TileGeometry("rt", T, H, W, th, tw, sh, sw, nr, nc, heads, d, dtype, 500 + H * 31 + W)
+    p = sg.make_problem(g, shift=(dy, dx))
+    tiles = [randn_tensor(g.tile_shape, dtype, g.seed + i).cuda() for i in range(g.n_tiles)]
+    out = torch.full(g.grid_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    sg.sg_tile_blend(p, tiles, out)
+    assert_close(to_f64(out), oracle.blend_shifted([to_f64(t) for t in tiles], g, dy, dx), dtype, "blend")
+    lat = randn_tensor(g.grid_shape, dtype, g.seed + 999).cuda()
+    ref = oracle.fuse_and_denoise([to_f64(t) for t in tiles], g, to_f64(lat), 1.0, 0.125, dy, dx)
+    sg.sg_tile_blend_update(p, tiles, lat, 1.0, 0.125, lat)
+    assert_close(to_f64(lat), ref, dtype, "update")
+    c = randn_tensor(g.grid_shape, dtype, g.seed + 5).cuda()
+    tr, tc = (g.seed * 3) % nr, (g.seed * 7) % nc
+    dst = torch.full((1,) + g.tile_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    sg.sg_tile_slice(p, [c], tr, tc, dst)
+    assert np.array_equal(to_f64(dst[0]), oracle.slice_tile_shifted(to_f64(c), g, tr, tc, dy, dx))

@@ -295,3 +295,35 @@ def test_bad_arguments_are_rejected():
     with pytest.raises(sg.SgError) as e:
         sg.sg_tile_attention(sg.make_problem(g), q, k, None, 0, 0, out)
     assert e.value.status == sg.SG_ERR_INVALID_ARG
+
+
+def _random_geometries(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        T = int(rng.integers(1, 4))
+        th, tw = int(rng.integers(2, 14)), int(rng.choice([3, 5, 8, 8, 12, 16, 16, 24, 7, 10]))
+        sh, sw = int(rng.integers(1, th + 1)), int(rng.integers(1, tw + 1))
+        nr, nc = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        H, W = (nr - 1) * sh + th, (nc - 1) * sw + tw
+        if T * th * tw > 900 or T * H * W > 6000:
+            continue
+        heads = int(rng.integers(1, 4))
+        out.append((T, H, W, th, tw, sh, sw, nr, nc, heads, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("geom", _random_geometries(36, 2024), ids=lambda t: "T%d_%dx%d_tile%dx%d_s%dx%d_%dx%d_h%d_%s" % (
+    t[0], t[1], t[2], t[3], t[4], t[5], t[6], t[7], t[8], t[9], "tm" if t[10] else "hm"))
+def test_attention_bf16_random_geometries(geom):
+    """Seeded random tilings (tile widths that are and are not multiples of 8, single tiles, token-major
+    canvases, key counts below and above one stage): the last tile and a random one against the oracle."""
+    T, H, W, th, tw, sh, sw, nr, nc, heads, token_major = geom
+    g = TileGeometry("rnd", T, H, W, th, tw, sh, sw, nr, nc, heads, 128, "bf16", 300 + T * 7 + H * 13 + W)
+    qkv = canvas_qkv(g)
+    dev = [t.permute(1, 2, 3, 0, 4).contiguous() for t in qkv] if token_major else qkv
+    p = sg.make_problem(g, token_major=token_major)
+    for tr, tc in {(nr - 1, nc - 1), ((g.seed * 3) % nr, (g.seed * 5) % nc)}:
+        out = torch.full(g.tile_shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        sg.sg_tile_attention(p, *dev, tr, tc, out)
+        assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv, tr, tc), "bf16", f"{geom} tile {tr},{tc}")
