@@ -20,7 +20,10 @@
  *     nothing and keeps no state between calls (scratch comes from the caller's workspace).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it and the calls return without waiting; no host readback takes place.
- *   - Inputs are never written.  Outputs must not alias inputs.
+ *   - Every call is a fixed sequence of kernel launches, so it can be captured in a HIP graph and
+ *     replayed.  The first bf16 attention launch on a device raises that kernel's dynamic-LDS limit
+ *     (a one-time function attribute): make one call outside of capture first.
+ *   - Inputs are never written.  Outputs must not alias inputs (exceptions are stated per call).
  *   - Argument checks run on the host before anything is launched; a failed check launches
  *     nothing.  Return value: SG_OK (0) or a negative sg_status.
  *   - Element types: SG_F32 (IEEE binary32) or SG_BF16 (bfloat16, round-to-nearest-even on
