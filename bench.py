@@ -104,11 +104,21 @@ def cpu_baseline(torch, g, x, rows_per_head, heads):
             }, rows, outs
 
 
-def full_extras(torch, sg, args):
-    """2K canvas step (9 tile attentions of 80,640 tokens + blend) and the gated 10-step 4K run."""
+def other_configs(torch, sg, args):
+    """The benchmark configurations besides the headline tile and the 4K step: the tiny fp32 step (config 1),
+    the 2K canvas step (config 3: 9 tile attentions of 80,640 tokens + blend) and the gated 10-step 4K run
+    (config 5).  Returns (figures, state kept for full_extras)."""
     from dataclasses import replace
     from synthetic import CONFIGS, eps_table, perturb_, randn_tensor
     res = {}
+    g1 = CONFIGS["tiny_f32"]
+    p1 = sg.make_problem(g1)
+    q1, k1, v1 = (torch.randn(g1.grid_shape, dtype=torch.float32, device="cuda") for _ in range(3))
+    tiles1 = [torch.empty(g1.tile_shape, dtype=torch.float32, device="cuda") for _ in range(g1.n_tiles)]
+    canvas1 = torch.empty(g1.grid_shape, dtype=torch.float32, device="cuda")
+    ms1 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p1, canvas1, tiles1, q=q1, k=k1, v=v1), 50, warmup=3)
+    res["step_tiny_f32"] = {"ms": round(ms1, 4), "tiles": g1.n_tiles, "note": "launch-latency bound: 4 attention launches + blend",
+                            "TFLOP/s": round(g1.attention_flops_per_tile * g1.n_tiles / ms1 * 1e-9, 4)}
     g3 = CONFIGS["canvas2k_bf16"]
     if args.heads:
         g3 = replace(g3, heads=args.heads)
@@ -152,7 +162,19 @@ def full_extras(torch, sg, args):
         e1.record()
         e1.synchronize()
         per_step.append({"ms": round(e0.elapsed_time(e1), 2), "recomputed": int(rec.sum())})
-    res["gated_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1), "steps": per_step}
+    res["gated_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1),
+                                "recomputed": sum(x["recomputed"] for x in per_step), "of": n5 * g5.steps, "steps": per_step}
+    return res, dict(g5=g5, p5=p5, n5=n5, tile_x=tile_x, cache_x=cache_x, cache_out=cache_out, scores=scores, rec=rec, ws=ws,
+                     canvas=canvas, eps=eps)
+
+
+def full_extras(torch, sg, args, kept):
+    """Inter-step cache policy figures at the 4K sizes: the refresh pass, ten steps through sg_refine_step, tile std."""
+    from synthetic import perturb_, randn_tensor
+    res = {}
+    g5, p5, n5, cache_out, scores, rec, ws, canvas, eps = (kept[k] for k in ("g5", "p5", "n5", "cache_out", "scores", "rec", "ws", "canvas", "eps"))
+    tile_x = cache_x = None
+    kept.pop("tile_x"); kept.pop("cache_x")
     del tile_x, cache_x
     # inter-step cache policy (gain, path length, residual reuse): the refresh pass alone, half the tiles
     # recomputed (reads O_t, O_{t-1}, I_t, writes delta: 10 B per element) and half reused (reads I_t, delta,
@@ -358,9 +380,25 @@ def main():
                               "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4g * 1e-9, 1),
                               "note": "tiles gathered into a packed workspace, then attended"}
         del q4, k4, v4, tiles4, canvas4, wsp
+        others, kept = other_configs(torch, sg, args)
+        kernels.update(others)
         if args.full:
-            kernels.update(full_extras(torch, sg, args))
+            kernels.update(full_extras(torch, sg, args, kept))
+        del kept
         out["kernels"] = kernels
+        frac = lambda tf: round(tf / PEAK_BF16_TFLOPS, 4)
+        out["configs"] = {
+            "1_tiny_f32_step": {"ms": kernels["step_tiny_f32"]["ms"], "TFLOP/s": kernels["step_tiny_f32"]["TFLOP/s"],
+                                "bound": "launch latency"},
+            "2_tile720p_bf16_step": {"ms": round(ms_step, 3), "TFLOP/s": round(value, 1), "frac_bf16_peak": frac(value)},
+            "3_canvas2k_bf16_step": {"ms": kernels["step_2k"]["ms"], "TFLOP/s": kernels["step_2k"]["TFLOP/s"],
+                                     "frac_bf16_peak": frac(kernels["step_2k"]["TFLOP/s"])},
+            "4_canvas4k_bf16_step": {"ms": kernels["step_4k"]["ms"], "TFLOP/s": kernels["step_4k"]["TFLOP/s"],
+                                     "frac_bf16_peak": frac(kernels["step_4k"]["TFLOP/s"])},
+            "5_canvas4k_gate_10_steps": {"ms": kernels["gated_4k_10_steps"]["total_ms"],
+                                         "recomputed_tiles": kernels["gated_4k_10_steps"]["recomputed"],
+                                         "of": kernels["gated_4k_10_steps"]["of"]},
+        }
         # measured achievable rates of this device, beside the vendor peaks the fractions are quoted against
         peaks = achievable_peaks()
         out["achievable_peaks"] = peaks

@@ -1,15 +1,18 @@
 // Tile attention, fp32 throughout (paper Section 2.1 "full attention" restricted to one tile).
 // Plain vector-ALU kernel for SG_F32 problems, where fp32 accuracy matters more than speed:
-// one thread owns one query row (q and o live in registers), keys and values are staged
-// through LDS 32 at a time and read back as wave-wide broadcasts, softmax is the online
-// (running max / running sum) form, which is algebraically the two-pass softmax.
+// a workgroup owns 64 query rows; its 4 wavefronts split the keys (each wavefront takes every
+// fourth 32-key chunk), one thread per query row and wavefront with q and o in registers, keys
+// and values staged through LDS and read back as wave-wide broadcasts, softmax in the online
+// (running max / running sum) form, which is algebraically the two-pass softmax.  The four
+// partial states (m, l, o) of a query are merged through LDS at the end.
 #include "sg_common.h"
 
 namespace sg {
 namespace {
 
-constexpr int kQ = 64;   // queries per workgroup = threads
-constexpr int kKC = 32;  // keys per LDS chunk
+constexpr int kQ = 64;       // queries per workgroup
+constexpr int kSplit = 4;    // wavefronts per workgroup, each on its own share of the keys
+constexpr int kKC = 32;      // keys per wavefront and LDS chunk
 
 __device__ __forceinline__ int64_t token_offset(const TileView& tv, int n) {
   const int plane = tv.th * tv.tw;
@@ -19,14 +22,18 @@ __device__ __forceinline__ int64_t token_offset(const TileView& tv, int n) {
 }
 
 template <int D>
-__global__ __launch_bounds__(kQ) void attention_f32_kernel(const TileView tv, const float scale, const float* __restrict__ q,
-                                                           const float* __restrict__ k, const float* __restrict__ v,
-                                                           float* __restrict__ out, const uint8_t* __restrict__ run_flag) {
+__global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileView tv, const float scale,
+                                                                    const float* __restrict__ q, const float* __restrict__ k,
+                                                                    const float* __restrict__ v, float* __restrict__ out,
+                                                                    const uint8_t* __restrict__ run_flag) {
   if (run_flag && !*run_flag) return;
-  __shared__ __attribute__((aligned(16))) float sK[kKC][D];
-  __shared__ __attribute__((aligned(16))) float sV[kKC][D];
+  // [wavefront][key][d] chunks of K and V; after the key loop the same memory holds the partial outputs
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float (*sK)[kKC][D] = (float (*)[kKC][D])smem;
+  float (*sV)[kKC][D] = (float (*)[kKC][D])(smem + kSplit * kKC * D);
   const int head = blockIdx.y;
-  const int n = blockIdx.x * kQ + threadIdx.x;
+  const int lane = threadIdx.x & (kQ - 1), wave = threadIdx.x / kQ;
+  const int n = blockIdx.x * kQ + lane;
   const bool valid = n < tv.N;
   const int64_t hoff = (int64_t)head * tv.stride_head;
 
@@ -44,18 +51,20 @@ __global__ __launch_bounds__(kQ) void attention_f32_kernel(const TileView tv, co
   float m = -__builtin_inff(), l = 0.f;
   constexpr float kLog2e = 1.4426950408889634f;
 
-  for (int m0 = 0; m0 < tv.N; m0 += kKC) {
+  // every wavefront loads and consumes its own chunk: no workgroup barrier inside the loop
+  for (int m0 = wave * kKC; m0 < tv.N; m0 += kSplit * kKC) {
     const int cnt = (tv.N - m0 < kKC) ? tv.N - m0 : kKC;
-    __syncthreads();
-    for (int e = threadIdx.x; e < kKC * (D / 4); e += kQ) {
+    for (int e = lane; e < kKC * (D / 4); e += kQ) {
       const int row = e / (D / 4), c4 = e - row * (D / 4);
       if (row < cnt) {
         const int64_t off = hoff + token_offset(tv, m0 + row);
-        ((float4*)sK[row])[c4] = ((const float4*)(k + off))[c4];
-        ((float4*)sV[row])[c4] = ((const float4*)(v + off))[c4];
+        ((float4*)sK[wave][row])[c4] = ((const float4*)(k + off))[c4];
+        ((float4*)sV[wave][row])[c4] = ((const float4*)(v + off))[c4];
       }
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     float s[kKC];
     float cmax = -__builtin_inff();
 #pragma unroll
@@ -64,7 +73,7 @@ __global__ __launch_bounds__(kQ) void attention_f32_kernel(const TileView tv, co
       if (r < cnt) {
 #pragma unroll
         for (int c = 0; c < D / 4; ++c) {
-          const float4 kk = ((const float4*)sK[r])[c];
+          const float4 kk = ((const float4*)sK[wave][r])[c];
           a0 = fmaf(qr[4 * c], kk.x, a0); a1 = fmaf(qr[4 * c + 1], kk.y, a1);
           a2 = fmaf(qr[4 * c + 2], kk.z, a2); a3 = fmaf(qr[4 * c + 3], kk.w, a3);
         }
@@ -86,19 +95,53 @@ __global__ __launch_bounds__(kQ) void attention_f32_kernel(const TileView tv, co
         l += p;
 #pragma unroll
         for (int c = 0; c < D / 4; ++c) {
-          const float4 vv = ((const float4*)sV[r])[c];
+          const float4 vv = ((const float4*)sV[wave][r])[c];
           o[4 * c] = fmaf(p, vv.x, o[4 * c]); o[4 * c + 1] = fmaf(p, vv.y, o[4 * c + 1]);
           o[4 * c + 2] = fmaf(p, vv.z, o[4 * c + 2]); o[4 * c + 3] = fmaf(p, vv.w, o[4 * c + 3]);
         }
       }
     }
     m = m_new;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();   // the chunk is consumed before the next one overwrites it
   }
-  if (valid) {
-    const float inv = 1.0f / l;
+
+  // ---- merge the kSplit partial states of every query: a wavefront that saw no key has m = -inf, l = 0
+  __syncthreads();
+  float* sM = smem;                          // [kSplit][kQ]
+  float* sL = smem + kSplit * kQ;            // [kSplit][kQ]
+  float* sO = smem + 2 * kSplit * kQ;        // [kSplit][D][kQ]  (query fastest: conflict-free)
+  sM[wave * kQ + lane] = m;
+  sL[wave * kQ + lane] = l;
+#pragma unroll
+  for (int c = 0; c < D; ++c) sO[(wave * D + c) * kQ + lane] = o[c];
+  __syncthreads();
+  if (wave == 0 && valid) {
+    float mt = sM[lane];
+#pragma unroll
+    for (int w = 1; w < kSplit; ++w) mt = fmaxf(mt, sM[w * kQ + lane]);
+    float lt = 0.f;
+    float wgt[kSplit];
+#pragma unroll
+    for (int w = 0; w < kSplit; ++w) {
+      const float mw = sM[w * kQ + lane];
+      wgt[w] = (mw == -__builtin_inff()) ? 0.f : exp2f((mw - mt) * kLog2e);
+      lt += wgt[w] * sL[w * kQ + lane];
+    }
+    const float inv = 1.0f / lt;
     float4* dst = (float4*)(out + ((int64_t)head * tv.N + n) * D);
 #pragma unroll
-    for (int c = 0; c < D / 4; ++c) dst[c] = make_float4(o[4 * c] * inv, o[4 * c + 1] * inv, o[4 * c + 2] * inv, o[4 * c + 3] * inv);
+    for (int c = 0; c < D / 4; ++c) {
+      float r4[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSplit; ++w) acc += wgt[w] * sO[(w * D + 4 * c + e) * kQ + lane];
+        r4[e] = acc * inv;
+      }
+      dst[c] = make_float4(r4[0], r4[1], r4[2], r4[3]);
+    }
   }
 }
 
@@ -106,10 +149,24 @@ __global__ __launch_bounds__(kQ) void attention_f32_kernel(const TileView tv, co
 
 int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const float* q, const float* k,
                          const float* v, float* out, const uint8_t* run_flag, hipStream_t s) {
+  if (head_dim != 64 && head_dim != 128) return SG_ERR_UNSUPPORTED;
   dim3 grid((tv.N + kQ - 1) / kQ, heads);
-  if (head_dim == 64) attention_f32_kernel<64><<<grid, kQ, 0, s>>>(tv, scale, q, k, v, out, run_flag);
-  else if (head_dim == 128) attention_f32_kernel<128><<<grid, kQ, 0, s>>>(tv, scale, q, k, v, out, run_flag);
-  else return SG_ERR_UNSUPPORTED;
+  // K and V chunks of the 4 wavefronts (2 * 4 * 32 * D floats); the merge reuses them for the partial
+  // outputs (4 * D * 64 floats, the same amount) and needs 2 * 4 * 64 floats more for the (m, l) pairs
+  const size_t lds = ((size_t)2 * kSplit * kKC * head_dim + 2 * kSplit * kQ) * sizeof(float);
+  static_assert(2 * kKC == kQ, "the merge buffer is sized by the chunk buffers");
+  constexpr int kMaxDevices = 64;
+  static bool attr_set[kMaxDevices][2] = {};
+  int dev = 0;
+  SG_HIP_TRY(hipGetDevice(&dev));
+  const int slot = head_dim == 64 ? 0 : 1;
+  const void* kern = head_dim == 64 ? (const void*)attention_f32_kernel<64> : (const void*)attention_f32_kernel<128>;
+  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot]) {
+    SG_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot] = true;
+  }
+  if (head_dim == 64) attention_f32_kernel<64><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
+  else attention_f32_kernel<128><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }
