@@ -46,6 +46,18 @@ def time_calls(torch, fn, reps, warmup=1):
     return e0.elapsed_time(e1) / reps      # ms per call
 
 
+def time_each(torch, fn, reps):
+    """Every call between its own pair of events: (min, median) in ms."""
+    ev = [_events(torch) for _ in range(reps)]
+    for e0, e1 in ev:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    t = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    return t[0], t[len(t) // 2]
+
+
 def counter_summary(name):
     """key = value lines of a committed rocprofv3 counter summary under profiles/ (None if absent)."""
     path = os.path.join(ROOT, "profiles", name)
@@ -99,9 +111,33 @@ def cpu_baseline(torch, g, x, rows_per_head, heads):
     outs = [oracle.attention_rows(host[0][a][rows], host[1][a], host[2][a], g.scale) for a in range(len(heads))]
     dt = time.perf_counter() - t0
     flops = 4.0 * len(rows) * len(heads) * N * d
+    full_s = dt * (N * g.heads) / (len(rows) * len(heads))
     return {"value": flops / dt * 1e-12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "sample": "%d query rows x %d heads of the %d-token tile, fp64 numpy, %.1f s" % (len(rows), len(heads), N, dt),
+            "extrapolated_full_tile_s": round(full_s, 1),
             }, rows, outs
+
+
+def cpu_baseline_streaming(torch, seed=7):
+    """The oracle's gate score and blend, timed on small samples (both are O(elements))."""
+    import numpy as np
+    import oracle
+    from synthetic import CONFIGS
+    rng = np.random.default_rng(seed)
+    n = 1 << 24
+    a, b = rng.standard_normal(n), rng.standard_normal(n)
+    t0 = time.perf_counter()
+    oracle.gate_score(a, b)
+    t_gate = time.perf_counter() - t0
+    g = CONFIGS["tiny_f32"]
+    tiles = [rng.standard_normal(g.tile_shape) for _ in range(g.n_tiles)]
+    t0 = time.perf_counter()
+    oracle.blend(tiles, g)
+    t_blend = time.perf_counter() - t0
+    elems = g.n_tiles * int(np.prod(g.tile_shape)) + int(np.prod(g.grid_shape))
+    return {"gate_elements_per_s": round(2 * n / t_gate, 1), "gate_sample": "2 x %d fp64 values, %.2f s" % (n, t_gate),
+            "blend_elements_per_s": round(elems / t_blend, 1),
+            "blend_sample": "config 1 (4 tiles -> 3x16x16 grid, 2 heads x 64), %.4f s" % t_blend}
 
 
 def other_configs(torch, sg, args):
@@ -312,6 +348,7 @@ def main():
         sg.sg_tile_attention(tile_problem, x[0], x[1], x[2], 0, 0, cache_out[0])
 
     ms_att = time_calls(torch, att, max(2, args.steps))
+    ms_att_min, ms_att_median = time_each(torch, att, 10)
     att_tflops = gt.attention_flops_per_tile / (ms_att * 1e-3) * 1e-12
     pmc = counter_summary("attention_bf16_tile720p_hbm_traffic.txt")
     traffic = None
@@ -329,6 +366,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(att_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                      "kernel": "attention_bf16_kernel", "ms_per_launch": round(ms_att, 3),
+                     "ms_min_of_10": round(ms_att_min, 3), "ms_median_of_10": round(ms_att_median, 3),
                      "flops_per_launch": gt.attention_flops_per_tile},
     }
     if args.heads:
@@ -406,6 +444,7 @@ def main():
             out["roofline"]["frac_of_measured_mfma_on_normal_data"] = round(att_tflops / peaks["mfma_bf16_normal_tflops"], 4)
         heads = sorted(set(np.linspace(0, gt.heads - 1, min(args.cpu_heads, gt.heads)).round().astype(int).tolist()))
         cb, rows, outs = cpu_baseline(torch, gt, x_a[0], args.cpu_rows if gt.tile_tokens > 10000 else 64, heads)
+        cb["streaming"] = cpu_baseline_streaming(torch)
         out["cpu_baseline"] = cb
         # the bench's own sanity check: GPU rows of the last attention launch against the oracle sample
         got = cache_out[0].reshape(gt.heads, gt.tile_tokens, gt.head_dim)
