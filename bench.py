@@ -58,6 +58,68 @@ def time_each(torch, fn, reps):
     return t[0], t[len(t) // 2]
 
 
+class DeviceStateSampler:
+    """Best-effort socket power and shader clock from sysfs while a timed region runs (None where unreadable)."""
+
+    def __init__(self, period_s=0.05):
+        import glob
+        self.power = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")
+                            + glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.cap = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+        self.sclk = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input"))
+        self.dpm = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.period, self.w, self.hz, self.stop = period_s, [], [], False
+
+    @staticmethod
+    def _read(paths):
+        for path in paths:
+            try:
+                with open(path) as f:
+                    return float(f.read().split()[0])
+            except (OSError, ValueError, IndexError):
+                continue
+        return None
+
+    def _read_dpm(self):
+        # lines like "1: 1650Mhz *": the starred level is the current one
+        for path in self.dpm:
+            try:
+                with open(path) as f:
+                    for line in f:
+                        if "*" in line:
+                            return float(line.split(":")[1].lower().split("mhz")[0]) * 1e6
+            except (OSError, ValueError, IndexError):
+                continue
+        return None
+
+    def _loop(self):
+        while not self.stop:
+            w, hz = self._read(self.power), self._read(self.sclk)
+            if hz is None:
+                hz = self._read_dpm()
+            if w is not None:
+                self.w.append(w * 1e-6)
+            if hz is not None:
+                self.hz.append(hz * 1e-6)
+            time.sleep(self.period)
+
+    def __enter__(self):
+        import threading
+        self.thread = threading.Thread(target=self._loop, daemon=True)
+        self.thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self.stop = True
+        self.thread.join()
+
+    def summary(self):
+        cap = self._read(self.cap)
+        mean = lambda v: round(sum(v) / len(v), 1) if v else None
+        return {"socket_power_w": mean(self.w), "power_cap_w": round(cap * 1e-6, 1) if cap else None,
+                "shader_clock_mhz": mean(self.hz), "samples": max(len(self.w), len(self.hz)), "source": "sysfs (hwmon, pp_dpm_sclk)"}
+
+
 def counter_summary(name):
     """key = value lines of a committed rocprofv3 counter summary under profiles/ (None if absent)."""
     path = os.path.join(ROOT, "profiles", name)
@@ -348,7 +410,8 @@ def main():
         sg.sg_tile_attention(tile_problem, x[0], x[1], x[2], 0, 0, cache_out[0])
 
     ms_att = time_calls(torch, att, max(2, args.steps))
-    ms_att_min, ms_att_median = time_each(torch, att, 10)
+    with DeviceStateSampler() as sampler:
+        ms_att_min, ms_att_median = time_each(torch, att, 10)
     att_tflops = gt.attention_flops_per_tile / (ms_att * 1e-3) * 1e-12
     pmc = counter_summary("attention_bf16_tile720p_hbm_traffic.txt")
     traffic = None
@@ -367,6 +430,7 @@ def main():
                      "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                      "kernel": "attention_bf16_kernel", "ms_per_launch": round(ms_att, 3),
                      "ms_min_of_10": round(ms_att_min, 3), "ms_median_of_10": round(ms_att_median, 3),
+                     "device_state_during_launches": sampler.summary(),
                      "flops_per_launch": gt.attention_flops_per_tile},
     }
     if args.heads:

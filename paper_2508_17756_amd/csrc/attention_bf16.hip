@@ -13,8 +13,8 @@
 // K and V rows are stored with XOR-swizzled 16-byte chunks so both fragment reads are free of bank
 // conflicts.
 //
-// The vector ALU, not the matrix pipe, limits this kernel, so the softmax is cut to one exponential,
-// one add and half a convert per score:  Q is pre-multiplied by log2(e)*scale (one bf16 rounding)
+// Vector work beside the MFMAs costs issue slots and, on a power-limited part, clock, so the softmax is
+// cut to one exponential, one add and half a convert per score:  Q is pre-multiplied by log2(e)*scale (one bf16 rounding)
 // and the score accumulators start at -M, the softmax reference, so the MFMA result is the
 // exponent itself.  M is an online-softmax running maximum refreshed lazily (see Softmax below).
 // A SIMD overlaps MFMA and vector work only across wavefronts, never inside one, so the two

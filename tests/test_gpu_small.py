@@ -40,6 +40,15 @@ def test_attention_f32_ragged(d):
     assert_close(to_f64(gpu_tile_attention(g, q, k, v, 0, 0)), oracle_tile_attention_full(g, q, k, v, 0, 0), "f32")
 
 
+@pytest.mark.parametrize("th,tw", [(1, 1), (3, 11), (7, 10), (3, 43), (8, 16), (13, 20)])
+def test_attention_f32_key_split(th, tw):
+    # N = 1, 33, 70, 129, 128, 260 tokens: the 4 wavefronts of a workgroup share the keys in chunks of 32,
+    # so these leave wavefronts without any key, with a partial chunk, and with unequal chunk counts
+    g = _geom("f32s", 1, th, tw, th, tw, th, tw, 2, 64, "f32", 300 + th * tw)
+    q, k, v = canvas_qkv(g)
+    assert_close(to_f64(gpu_tile_attention(g, q, k, v, 0, 0)), oracle_tile_attention_full(g, q, k, v, 0, 0), "f32")
+
+
 BF16_CASES = [
     # name, T, H, W, th, tw, sh, sw, heads: packed tiles (linear addressing) and canvas views
     ("packed_n576", 3, 12, 16, 12, 16, 12, 16, 2),      # 576 = 2*256 + 64, 9 full key blocks
