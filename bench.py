@@ -337,7 +337,7 @@ def main():
     ap.add_argument("--workload", default="tile720p_bf16")
     ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
     ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
-    ap.add_argument("--full", action="store_true", help="also time the 2K canvas step and the gated 10-step 4K run")
+    ap.add_argument("--full", action="store_true", help="also time the gain refresh, the 10-step refine run and the tile statistics at the 4K sizes")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="query rows per head of the CPU baseline sample")
     ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the CPU baseline sample")
     args = ap.parse_args()
