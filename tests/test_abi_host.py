@@ -90,3 +90,36 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_tile_slice(ctypes.byref(ps), arr, 2, 2, 0, 256, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, None, 1.0, 0.1, 256, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, 256, float("nan"), 0.1, 256, None) == sg.SG_ERR_INVALID_ARG
+
+
+def test_plain_c_client_compiles_links_and_agrees_on_layout(repo_root, tmp_path):
+    """The header is C: a C99 translation unit with -pedantic -Werror includes it, links against the
+    library and calls the host-only entry points; the sizes the C compiler derives are the binding's."""
+    import os
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    sg.load_library()
+    libdir = f"{repo_root}/paper_2508_17756_amd"
+    exe = str(tmp_path / "host_client")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", f"-I{repo_root}/include",
+                    f"{repo_root}/tests/c_client/host_client.c", "-o", exe, f"-L{libdir}", "-lsupergen_tile",
+                    f"-Wl,-rpath,{libdir}"], check=True, capture_output=True, text=True)
+    env = dict(os.environ)
+    run = subprocess.run([exe], check=True, capture_output=True, text=True, env=env, timeout=120)
+    kv = dict(line.split("=", 1) for line in run.stdout.strip().splitlines())
+    assert kv["version"] == sg.sg_version()
+    assert int(kv["sizeof_problem"]) == ctypes.sizeof(sg.sg_problem)
+    assert int(kv["offset_stride_token"]) == sg.sg_problem.grid_stride_token.offset
+    assert int(kv["offset_shift_h"]) == sg.sg_problem.shift_h.offset
+    assert int(kv["sizeof_step_io"]) == ctypes.sizeof(sg.sg_step_io)
+    assert int(kv["sizeof_gain_state"]) == ctypes.sizeof(sg.sg_gain_state)
+    assert int(kv["sizeof_gain_step_io"]) == ctypes.sizeof(sg.sg_gain_step_io)
+    assert int(kv["sizeof_region_control"]) == ctypes.sizeof(sg.sg_region_control)
+    assert int(kv["sizeof_scheduler_update"]) == ctypes.sizeof(sg.sg_scheduler_update)
+    assert int(kv["validate"]) == sg.SG_OK and int(kv["validate_gap"]) == sg.SG_ERR_INVALID_ARG
+    assert int(kv["workspace_status"]) == sg.SG_OK and int(kv["workspace_bytes"]) == sg.sg_workspace_bytes(20)
+    assert int(kv["null_attention"]) == int(kv["null_blend"]) == int(kv["null_step"]) == sg.SG_ERR_INVALID_ARG
+    assert kv["status_string"] == "invalid argument"
