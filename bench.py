@@ -516,6 +516,16 @@ def main():
         gpu = got[heads][:, torch.as_tensor(rows, device="cuda")].to("cpu").to(torch.float64).numpy()
         out["parity_sample"] = {"max_abs": float(np.abs(gpu - ref).max()),
                                 "rel_l2": float(np.linalg.norm(gpu - ref) / np.linalg.norm(ref))}
+    # the paper's own figures, for context only: other hardware, whole model, never a target or a ratio
+    out["paper_context"] = {
+        "this_path": "the paper reports no attention TFLOP/s, blend bandwidth, gate cost or per-step time",
+        "surrounding": {
+            "stage_2_refinement_s": {"2K_1gpu": 534, "4K_1gpu": 1408, "4K_8gpu": 321,
+                                     "what": "CogVideoX-1.5 5B, 45 steps, whole DiT forward per tile, no cache (Table 6)"},
+            "cache_speedup_2K_1gpu": {"CogVideoX-1.5": 1.46, "HunyuanVideo": 1.97, "what": "latency without / with cache (Table 4)"},
+        },
+        "hardware": "NVIDIA H100-80GB, 8 per node with NVLink (Section 8)",
+    }
     print(json.dumps(out))
 
 
