@@ -338,6 +338,19 @@ typedef struct sg_scheduler_update {
 int sg_refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
                    const sg_scheduler_update* update, void* stream);
 
+/* The whole loop body of Algorithm 1 from canvas tensors: Shift (the partition sits at
+ * p->shift_h, p->shift_w, wrapping) and SliceTile of every tile, then sg_refine_step.
+ *   q, k, v   device, canvas tensors (addressed through p's strides); read only
+ *   tile_x    host array of n_tiles device pointers to WRITABLE buffers of
+ *             3 * heads * T * tile_h * tile_w * head_dim elements: tile i's window of q, k and v is
+ *             gathered into tile_x[i] before anything else; io->tile_x must name the same buffers
+ *             (SG_ERR_INVALID_ARG otherwise) and io->prev_x the ones the previous call filled, so a
+ *             caller alternates two sets of buffers.  Must not alias q, k, v or any output.
+ * io, region, update, errors: as sg_refine_step. */
+int sg_refine_step_canvas(const sg_problem* p, const void* q, const void* k, const void* v, void* const* tile_x,
+                          const sg_gain_step_io* io, const sg_region_control* region,
+                          const sg_scheduler_update* update, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

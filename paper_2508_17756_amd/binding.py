@@ -125,6 +125,9 @@ def load_library():
     lib.sg_refine_step.restype = ctypes.c_int
     lib.sg_refine_step.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_gain_step_io),
                                    ctypes.POINTER(sg_region_control), ctypes.POINTER(sg_scheduler_update), vp]
+    lib.sg_refine_step_canvas.restype = ctypes.c_int
+    lib.sg_refine_step_canvas.argtypes = [ctypes.POINTER(sg_problem), vp, vp, vp, pp, ctypes.POINTER(sg_gain_step_io),
+                                          ctypes.POINTER(sg_region_control), ctypes.POINTER(sg_scheduler_update), vp]
     lib.sg_tile_std.restype = ctypes.c_int
     lib.sg_tile_std.argtypes = [pp, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]
     lib.sg_region_thresholds.restype = ctypes.c_int
@@ -314,9 +317,12 @@ def sg_gain_refresh(out_cur, out_prev, latent, delta, recompute, step_change, st
 
 
 def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, state, threshold, step_change,
-                         scores, recompute, workspace, latent=None, tile_thresholds=None, region=None, update=None):
+                         scores, recompute, workspace, latent=None, tile_thresholds=None, region=None, update=None,
+                         canvas=None):
     """region: dict(track_mean, track_count, tile_std, thresholds, tau_base, alpha, mode, adjust[, sigma]);
-    update: dict(latent_in, latent_out, c_latent, c_noise).  With either one the call goes to sg_refine_step."""
+    update: dict(latent_in, latent_out, c_latent, c_noise).  With either one the call goes to sg_refine_step.
+    canvas: (q, k, v) canvas tensors; the call goes to sg_refine_step_canvas, which first gathers every
+    tile's window (under p's shift) into tile_x."""
     io = sg_gain_step_io()
     keep = [_ptr_array(tile_x), _ptr_array(prev_x), _ptr_array(out_cur), _ptr_array(out_prev), _ptr_array(delta)]
     io.tile_x, io.prev_x, io.out_cur, io.out_prev, io.delta = keep
@@ -329,7 +335,7 @@ def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, 
     io.step_change, io.scores, io.recompute = _ptr(step_change), _ptr(scores), _ptr(recompute)
     io.grid_out = _ptr(grid_out)
     io.workspace, io.workspace_bytes = _ptr(workspace), _nbytes(workspace)
-    if region is None and update is None:
+    if region is None and update is None and canvas is None:
         rc = load_library().sg_denoise_step_gain(ctypes.byref(p), ctypes.byref(io), _stream())
         _check(rc, "sg_denoise_step_gain")
         return grid_out
@@ -344,9 +350,16 @@ def sg_denoise_step_gain(p, grid_out, tile_x, prev_x, out_cur, out_prev, delta, 
         up = sg_scheduler_update()
         up.latent_in, up.latent_out = _ptr(update["latent_in"]), _ptr(update["latent_out"])
         up.c_latent, up.c_noise = float(update["c_latent"]), float(update["c_noise"])
-    rc = load_library().sg_refine_step(ctypes.byref(p), ctypes.byref(io), ctypes.byref(rg) if rg is not None else None,
-                                       ctypes.byref(up) if up is not None else None, _stream())
-    _check(rc, "sg_refine_step")
+    rg_ref = ctypes.byref(rg) if rg is not None else None
+    up_ref = ctypes.byref(up) if up is not None else None
+    if canvas is not None:
+        q, k, v = canvas
+        rc = load_library().sg_refine_step_canvas(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), keep[0], ctypes.byref(io),
+                                                  rg_ref, up_ref, _stream())
+        _check(rc, "sg_refine_step_canvas")
+    else:
+        rc = load_library().sg_refine_step(ctypes.byref(p), ctypes.byref(io), rg_ref, up_ref, _stream())
+        _check(rc, "sg_refine_step")
     return update["latent_out"] if update is not None else grid_out
 
 

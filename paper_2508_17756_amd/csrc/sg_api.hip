@@ -270,8 +270,8 @@ int sg_gain_refresh(void* const* out_cur, const void* const* out_prev, const voi
                              dtype, workspace, (hipStream_t)stream);
 }
 
-static int refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
-                       const sg_scheduler_update* update, void* stream) {
+static int refine_step_check(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
+                             const sg_scheduler_update* update) {
   int st = validate(p);
   if (st != SG_OK) return st;
   if (!io) return SG_ERR_INVALID_ARG;
@@ -298,6 +298,14 @@ static int refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_
   if (io->latent && check_ptr_array(io->latent, n_tiles) != SG_OK) return SG_ERR_INVALID_ARG;
   if (!io->workspace || (((uintptr_t)io->workspace) & 255u) || io->workspace_bytes < gate_workspace_bytes(n_tiles))
     return SG_ERR_WORKSPACE;
+  return SG_OK;
+}
+
+static int refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
+                       const sg_scheduler_update* update, void* stream) {
+  int st = refine_step_check(p, io, region, update);
+  if (st != SG_OK) return st;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
   hipStream_t s = (hipStream_t)stream;
   const size_t esz = p->dtype == SG_BF16 ? 2 : 4;
   const int64_t tile_elems = (int64_t)p->heads * p->T * p->tile_h * p->tile_w * p->head_dim;
@@ -341,6 +349,28 @@ int sg_denoise_step_gain(const sg_problem* p, const sg_gain_step_io* io, void* s
 
 int sg_refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_region_control* region,
                    const sg_scheduler_update* update, void* stream) {
+  return refine_step(p, io, region, update, stream);
+}
+
+int sg_refine_step_canvas(const sg_problem* p, const void* q, const void* k, const void* v, void* const* tile_x,
+                          const sg_gain_step_io* io, const sg_region_control* region,
+                          const sg_scheduler_update* update, void* stream) {
+  int st = validate(p);
+  if (st != SG_OK) return st;
+  if (!q || !k || !v || !aligned16(q) || !aligned16(k) || !aligned16(v) || !tile_x || !io || !io->tile_x)
+    return SG_ERR_INVALID_ARG;
+  const int n_tiles = p->n_tile_rows * p->n_tile_cols;
+  for (int i = 0; i < n_tiles; ++i)
+    if (!tile_x[i] || !aligned16(tile_x[i]) || io->tile_x[i] != tile_x[i]) return SG_ERR_INVALID_ARG;
+  // every check of the step itself runs before the first launch: a rejected call leaves tile_x untouched
+  st = refine_step_check(p, io, region, update);
+  if (st != SG_OK) return st;
+  const void* src[3] = {q, k, v};
+  for (int tr = 0; tr < p->n_tile_rows; ++tr)
+    for (int tc = 0; tc < p->n_tile_cols; ++tc) {
+      st = launch_slice(*p, src, 3, tr, tc, tile_x[tr * p->n_tile_cols + tc], (hipStream_t)stream);
+      if (st != SG_OK) return st;
+    }
   return refine_step(p, io, region, update, stream);
 }
 

@@ -92,6 +92,20 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, 256, float("nan"), 0.1, 256, None) == sg.SG_ERR_INVALID_ARG
 
 
+def test_canvas_refine_step_wants_its_own_tile_buffers():
+    lib = sg.load_library()
+    p = sg.make_problem(CONFIGS["tiny_f32"])            # 4 tiles
+    mine = (ctypes.c_void_p * 4)(256, 512, 768, 1024)
+    other = (ctypes.c_void_p * 4)(256, 512, 768, 2048)
+    io = sg.sg_gain_step_io()
+    io.tile_x = other
+    assert lib.sg_refine_step_canvas(ctypes.byref(p), 16, 16, 16, mine, ctypes.byref(io), None, None, None) == sg.SG_ERR_INVALID_ARG
+    io.tile_x = mine    # the same buffers, but the step's own arguments are incomplete
+    assert lib.sg_refine_step_canvas(ctypes.byref(p), 16, 16, 16, mine, ctypes.byref(io), None, None, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_refine_step_canvas(ctypes.byref(p), None, 16, 16, mine, ctypes.byref(io), None, None, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_refine_step_canvas(ctypes.byref(p), 16, 16, 16, None, ctypes.byref(io), None, None, None) == sg.SG_ERR_INVALID_ARG
+
+
 def test_plain_c_client_compiles_links_and_agrees_on_layout(repo_root, tmp_path):
     """The header is C: a C99 translation unit with -pedantic -Werror includes it, links against the
     library and calls the host-only entry points; the sizes the C compiler derives are the binding's."""

@@ -202,3 +202,80 @@ def test_blend_slice_update_random_tilings(case):
     dst = torch.full((1,) + g.tile_shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
     sg.sg_tile_slice(p, [c], tr, tc, dst)
     assert np.array_equal(to_f64(dst[0]), oracle.slice_tile_shifted(to_f64(c), g, tr, tc, dy, dx))
+
+
+def test_refine_step_from_canvas_tensors_under_moving_partitions():
+    """sg_refine_step_canvas = Shift + SliceTile of every tile + sg_refine_step: bit for bit the same as
+    sg_tile_slice per tile followed by sg_refine_step, over four steps whose partition moves every step; the
+    first step (every tile recomputed) is also checked against the oracle end to end."""
+    g = _geom("rc", 2, 16, 24, 8, 12, 8, 12, 2, 128, "bf16", 41)         # 2 x 2 non-overlapping tiles, as in the paper
+    n, E = g.n_tiles, int(np.prod(g.tile_shape))
+    shifts = [(0, 0), (3, 7), (6, 14), (9, 21)]
+    qkv = [randn_tensor(g.grid_shape, "bf16", g.seed + 5 * s).cuda() for s in range(3)]
+    qkv0 = [to_f64(t) for t in qkv]
+
+    def fresh():
+        return dict(x=[[torch.zeros((3,) + g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)],
+                    outs=[[torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)],
+                    delta=[torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)],
+                    state=sg.GainState(n),
+                    step_change=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    scores=torch.zeros(n, dtype=torch.float32, device="cuda"),
+                    rec=torch.zeros(n, dtype=torch.uint8, device="cuda"),
+                    ws=torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda"),
+                    latent=randn_tensor(g.grid_shape, "bf16", 778).cuda())
+
+    a, b = fresh(), fresh()
+    latent0 = to_f64(a["latent"])
+    gen = torch.Generator(device="cuda")
+    for k, shift in enumerate(shifts):
+        p = sg.make_problem(g, shift=shift)
+        if k:   # the canvas drifts a little between the steps
+            gen.manual_seed(4100 + k)
+            for t in qkv:
+                t.add_((0.01 * torch.randn(t.shape, generator=gen, device="cuda", dtype=torch.float32)).to(t.dtype))
+        coef = (1.0, -0.1 * (k + 1))
+        upd = lambda d: dict(latent_in=d["latent"], latent_out=d["latent"], c_latent=coef[0], c_noise=coef[1])
+        cur, prev = k % 2, (k + 1) % 2
+        # (a) one call from the canvas tensors
+        sg.sg_denoise_step_gain(p, None, a["x"][cur], a["x"][prev], a["outs"][cur], a["outs"][prev], a["delta"], a["state"],
+                                0.05, a["step_change"], a["scores"], a["rec"], a["ws"], update=upd(a), canvas=qkv)
+        # (b) the parts
+        for tr in range(g.n_tile_rows):
+            for tc in range(g.n_tile_cols):
+                sg.sg_tile_slice(p, qkv, tr, tc, b["x"][cur][tr * g.n_tile_cols + tc])
+        sg.sg_denoise_step_gain(p, None, b["x"][cur], b["x"][prev], b["outs"][cur], b["outs"][prev], b["delta"], b["state"],
+                                0.05, b["step_change"], b["scores"], b["rec"], b["ws"], update=upd(b))
+        torch.cuda.synchronize()
+        for key in ("step_change", "scores", "rec", "latent"):
+            assert torch.equal(a[key], b[key]), (k, key)
+        for ta, tb in zip(a["x"][cur] + a["outs"][cur] + a["delta"], b["x"][cur] + b["outs"][cur] + b["delta"]):
+            assert torch.equal(ta, tb), k
+        if k == 0:
+            assert a["rec"].cpu().tolist() == [1] * n
+            outs = []
+            for tr in range(g.n_tile_rows):
+                for tc in range(g.n_tile_cols):
+                    Q, K, V = (oracle.slice_tile_shifted(t, g, tr, tc, *shift) for t in qkv0)
+                    outs.append(np.stack([oracle.attention(Q[h].reshape(-1, 128), K[h].reshape(-1, 128),
+                                                           V[h].reshape(-1, 128), g.scale)
+                                          for h in range(g.heads)]).reshape(g.tile_shape))
+            assert_close(to_f64(a["latent"]), oracle.fuse_and_denoise(outs, g, latent0, coef[0], coef[1], *shift), "bf16", "latent")
+
+
+def test_refine_step_canvas_rejected_call_gathers_nothing():
+    g = _geom("rc", 2, 16, 24, 8, 12, 8, 12, 2, 128, "bf16", 41)
+    n, E = g.n_tiles, int(np.prod(g.tile_shape))
+    p = sg.make_problem(g)
+    qkv = [torch.zeros(g.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    x = [[torch.zeros((3,) + g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)]
+    outs = [[torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for _ in range(2)]
+    delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)]
+    f = lambda: torch.zeros(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    grid = torch.zeros(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sg.SgError):      # no workspace: rejected before any tile is gathered
+        sg.sg_denoise_step_gain(p, grid, x[0], x[1], outs[0], outs[1], delta, sg.GainState(n), 0.05, f(), f(),
+                                torch.zeros(n, dtype=torch.uint8, device="cuda"), None, canvas=qkv)
+    torch.cuda.synchronize()
+    assert all(int(t.abs().sum()) == 0 for t in x[0])
