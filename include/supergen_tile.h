@@ -69,7 +69,7 @@ typedef struct sg_problem {
   int32_t tile_h, tile_w;           /* tile size in tokens (a tile spans all T)                */
   int32_t stride_h, stride_w;       /* spacing of tile origins; overlap = tile - stride >= 0   */
   int32_t n_tile_rows, n_tile_cols; /* (n-1)*stride + tile must equal H (resp. W)              */
-  int32_t heads, head_dim;          /* head_dim: 64 or 128                                     */
+  int32_t heads, head_dim;          /* head_dim: 64 or 128 (either dtype)                      */
   int32_t dtype;                    /* sg_dtype of every tensor of the problem                 */
   float scale;                      /* softmax scale applied to Q.K^T, > 0 (1/sqrt(head_dim))  */
   int64_t grid_stride_token;        /* canvas tensors: elements between consecutive tokens     */

@@ -573,6 +573,9 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 
 int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
                           const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
+  // head_dim 64 (half-length rows) is served by the register-staged kernel; the streaming kernel below is
+  // laid out for 256-byte rows
+  if (head_dim == 64) return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
   if (head_dim != 128) return SG_ERR_UNSUPPORTED;
   View16 vw;
   vw.base16 = (uint32_t)(tv.base / 8);

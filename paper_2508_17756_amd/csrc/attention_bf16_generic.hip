@@ -1,9 +1,10 @@
 // Tile attention on the matrix cores, general-addressing variant (paper Section 2.1 "full
 // attention" over one tile's T x tile_h x tile_w tokens; Section 3: tiles exchange no Q/K/V).
 // Used for canvases whose per-head extent exceeds the 32-bit byte offsets of the streaming kernel
-// in attention_bf16.hip; slower (register-staged loads, in-step barriers), same mathematics.
+// in attention_bf16.hip, and for head_dim 64 (the streaming kernel is laid out for head_dim 128);
+// slower (register-staged loads, in-step barriers), same mathematics.
 //
-// Flash-style: a workgroup owns 256 query rows of one head (4 wavefronts x 64 rows) and streams
+// Flash-style: a workgroup owns 256 query rows of one head (8 wavefronts x 32 rows) and streams
 // the tile's keys and values through LDS 64 at a time; the N x N score matrix is never stored.
 // All products are bf16 MFMA (32x32x16) with fp32 accumulation, softmax statistics are fp32.
 //
@@ -72,6 +73,8 @@ __device__ __forceinline__ void cursor_advance(const View16& vw, RowCursor& c, i
 
 // LDS stage: K[64][128] then V[64][128] bf16, rows of 256 bytes = 16 chunks of 16 bytes.
 // K chunk c of row r is stored at chunk c ^ (r & 15); V chunk c of row r at c ^ ((r & 3) << 2).
+// With head_dim 64 a row has 8 chunks and keeps its 256-byte slot: the XOR still sends them to distinct
+// positions below 16.
 constexpr int kRowBytes = 256;
 constexpr int kStageBytes = 2 * kBC * kRowBytes;  // 32 KiB
 
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
                                                                   const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
                                                                   const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
                                                                   const uint8_t* __restrict__ run_flag) {
-  static_assert(D == 128 && kQB == 1 && kBC == 64, "head_dim 128, one 32-query block per wavefront, 64-key stages");
+  static_assert((D == 128 || D == 64) && kQB == 1 && kBC == 64, "head_dim 64 or 128, one 32-query block per wavefront, 64-key stages");
   if (run_flag && !*run_flag) return;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
@@ -170,9 +173,12 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
     for (int kk = 0; kk < D / 16; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, src[2 * kk + half]);
   }
 
-  // ---- K/V loader: thread owns chunk (tid & 15) of rows (tid >> 4) + kLdRows*u, u < kLdSlots, of every stage
-  const int ld_chunk = tid & 15, ld_row = tid >> 4;
-  constexpr int kLdRows = kThreads / 16, kLdSlots = kBC / kLdRows;
+  // ---- K/V loader: a row has D/8 chunks of 16 bytes; thread owns chunk (tid % kChunks) of rows
+  // (tid / kChunks) + kLdRows*u, u < kLdSlots, of every stage
+  constexpr int kChunks = D / 8;
+  const int ld_chunk = tid % kChunks, ld_row = tid / kChunks;
+  constexpr int kLdRows = kThreads / kChunks, kLdSlots = kBC / kLdRows;
+  static_assert(kLdSlots >= 1 && kLdRows * kLdSlots == kBC, "the workgroup's threads tile a stage exactly");
   RowCursor cur[kLdSlots];
   uint32_t last16;
   {
@@ -307,7 +313,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
 
 int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
                           const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
-  if (head_dim != 128) return SG_ERR_UNSUPPORTED;
+  if (head_dim != 128 && head_dim != 64) return SG_ERR_UNSUPPORTED;
   View16 vw;
   vw.base16 = (uint32_t)(tv.base / 8);
   vw.st16 = (uint32_t)(tv.stride_token / 8);
@@ -322,17 +328,16 @@ int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, f
   const float c_log2 = scale * 1.4426950408889634f;
   const size_t lds = 2 * kStageBytes;
   dim3 grid(per_xcd * kXcd);
-  if (linear) {
-    auto kern = attention_bf16_generic_kernel<128, true>;
+  auto launch = [&](auto kern) -> int {
     SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
                                      (const u32x4*)v, (uint16_t*)out, run_flag);
-  } else {
-    auto kern = attention_bf16_generic_kernel<128, false>;
-    SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                     (const u32x4*)v, (uint16_t*)out, run_flag);
-  }
+    return SG_OK;
+  };
+  int st;
+  if (head_dim == 128) st = linear ? launch(attention_bf16_generic_kernel<128, true>) : launch(attention_bf16_generic_kernel<128, false>);
+  else st = linear ? launch(attention_bf16_generic_kernel<64, true>) : launch(attention_bf16_generic_kernel<64, false>);
+  if (st != SG_OK) return st;
   SG_HIP_TRY(hipGetLastError());
   return SG_OK;
 }

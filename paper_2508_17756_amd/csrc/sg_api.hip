@@ -27,7 +27,6 @@ static int validate(const sg_problem* p) {
   if (p->grid_stride_token < p->head_dim || p->grid_stride_head <= 0) return SG_ERR_INVALID_ARG;
   if ((p->grid_stride_token & 7) || (p->grid_stride_head & 7)) return SG_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return SG_ERR_UNSUPPORTED;
-  if (p->dtype == SG_BF16 && p->head_dim != 128) return SG_ERR_UNSUPPORTED;
   if ((int64_t)p->n_tile_rows * p->n_tile_cols > SG_MAX_TILES) return SG_ERR_UNSUPPORTED;
   if ((int64_t)p->T * p->tile_h * p->tile_w >= (1ll << 31)) return SG_ERR_UNSUPPORTED;
   if ((int64_t)p->heads * p->T >= 65536) return SG_ERR_UNSUPPORTED;

@@ -73,6 +73,28 @@ def test_attention_bf16_small(case):
         print(f"{name} tile({tr},{tc}) max_abs={ma:.2e} rel_l2={rl:.2e}")
 
 
+@pytest.mark.parametrize("case", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_attention_bf16_head_dim_64(case):
+    """head_dim 64 (the head width of CogVideoX-1.5, Section 8 "Workloads") in bf16: the same cases through the
+    register-staged kernel, packed and in place."""
+    name, T, H, W, th, tw, sh, sw, heads = case
+    g = _geom(name, T, H, W, th, tw, sh, sw, heads, 64, "bf16", 23)
+    q, k, v = canvas_qkv(g)
+    for tr, tc in {(0, 0), (g.n_tile_rows - 1, g.n_tile_cols - 1)}:
+        got = gpu_tile_attention(g, q, k, v, tr, tc)
+        assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, tr, tc), "bf16", f"{name} {tr},{tc}")
+
+
+def test_step_bf16_head_dim_64():
+    g = _geom("d64step", 2, 14, 20, 8, 12, 6, 8, 3, 64, "bf16", 25)
+    q, k, v = canvas_qkv(g)
+    outs = [torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
+    canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    sg.sg_denoise_step_tiled(sg.make_problem(g), canvas, outs, q=q, k=k, v=v)
+    ref = [oracle_tile_attention_full(g, q, k, v, tr, tc) for tr in range(g.n_tile_rows) for tc in range(g.n_tile_cols)]
+    assert_close(to_f64(canvas), oracle.blend(ref, g), "bf16")
+
+
 def test_attention_bf16_token_major_layout():
     """[T][H][W][heads][d] canvas through the stride fields."""
     g = _geom("tokmaj", 2, 12, 18, 8, 10, 4, 8, 3, 128, "bf16", 31)
