@@ -34,6 +34,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #define SG_LDS __attribute__((address_space(3)))
+#define SG_INLINE __attribute__((always_inline))   // on the kernel's lambdas: a lambda left as a call pins every captured array in memory
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
@@ -101,27 +102,37 @@ __device__ __forceinline__ void meet() {  // workgroup barrier that nothing is s
 // exponential of a stage exceeds 2^16 the reference stays, so the common path needs no row maximum, no
 // subtraction and no rescaling of the output accumulators; the result is the same softmax, since any
 // common reference cancels in sum(p v) / sum(p).
+// Score and probability arrays have this fixed extent for either head_dim (NB <= kMaxSB blocks are used):
+// their types then do not depend on a template parameter, which the register-pinning asm statements need.
+constexpr int kMaxSB = 4;
+
 struct Softmax {
   float M;   // reference, log2 domain
   float l;   // this lane's share of sum(p)
 };
 
-__device__ __forceinline__ void mask_tail(f32x16 (&t)[2], const int key0, const int n_keys) {
+// Scores of keys at or beyond n_keys become -inf.  Branch- and compare-free (sign mask + bit select), so the
+// 16 NB decisions do not each occupy a pair of scalar registers.
+template <int NB>
+__device__ __forceinline__ void mask_tail(f32x16 (&t)[kMaxSB], const int key0, const int n_keys) {
   const int half = (threadIdx.x & 63) >> 5;
+  const int limit = n_keys - key0 - 4 * half;   // register (kb, r) holds key offset 32 kb + 8 (r >> 2) + (r & 3)
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (key >= n_keys) t[kb][r] = -__builtin_inff();
+      const int c = 32 * kb + 8 * (r >> 2) + (r & 3);
+      const uint32_t beyond = (uint32_t)((limit - 1 - c) >> 31);   // all ones if c >= limit
+      t[kb][r] = __uint_as_float((__float_as_uint(t[kb][r]) & ~beyond) | (0xff800000u & beyond));
     }
 }
 
 // p[2 kb + h] = bf16(exp2(t[kb][8h..8h+7])) in B-operand order; returns this lane's sum of the exponentials
-__device__ __forceinline__ float exp_block(const f32x16 (&t)[2], bf16x8 (&p)[4]) {
+template <int NB>
+__device__ __forceinline__ float exp_block(const f32x16 (&t)[kMaxSB], bf16x8 (&p)[2 * kMaxSB]) {
   float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       float e[8];
@@ -135,14 +146,25 @@ __device__ __forceinline__ float exp_block(const f32x16 (&t)[2], bf16x8 (&p)[4])
   return sum0 + sum1;
 }
 // row maximum of the stage for this lane's query, combined over both halves of the wavefront
-__device__ __forceinline__ float block_max(const f32x16 (&t)[2]) {
+template <int NB>
+__device__ __forceinline__ float block_max(const f32x16 (&t)[kMaxSB]) {
   float mx0 = t[0][0], mx1 = t[1][0];
 #pragma unroll
   for (int r = 1; r < 15; r += 2) {
     mx0 = fmaxf(fmaxf(mx0, t[0][r]), t[0][r + 1]);
     mx1 = fmaxf(fmaxf(mx1, t[1][r]), t[1][r + 1]);
   }
-  const float mx = fmaxf(fmaxf(mx0, t[0][15]), fmaxf(mx1, t[1][15]));
+  mx0 = fmaxf(mx0, t[0][15]);
+  mx1 = fmaxf(mx1, t[1][15]);
+#pragma unroll
+  for (int kb = 2; kb < NB; ++kb) {
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      if (kb & 1) mx1 = fmaxf(fmaxf(mx1, t[kb][r]), t[kb][r + 1]);
+      else mx0 = fmaxf(fmaxf(mx0, t[kb][r]), t[kb][r + 1]);
+    }
+  }
+  const float mx = fmaxf(mx0, mx1);
   const uint32_t mu = __float_as_uint(mx);
   const auto sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
   return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
@@ -157,7 +179,14 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
                                                                   const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
                                                                   const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
                                                                   const uint8_t* __restrict__ run_flag) {
-  static_assert(D == 128, "head_dim 128");
+  static_assert(D == 128 || D == 64, "head_dim 64 or 128");
+  static_assert(D == 128 || MODE == kLinear, "head_dim 64 streams packed tiles only");
+  // LDS rows ("slots") are always 256 bytes.  With head_dim 128 a slot is one key and a stage 64 keys; with
+  // head_dim 64 a stage is 128 keys and slot 32 g + r holds key 64 g + r in its first half and key
+  // 64 g + 32 + r in its second, so the fragment reads and the MFMA count per stage are the same and only
+  // the pairing of fragments with accumulators differs (see qk and pv).
+  constexpr int kSB = (D == 128) ? 2 : 4;   // 32-key score blocks per stage
+  constexpr int kKeys = 32 * kSB;           // keys per stage
   if (run_flag && !*run_flag) return;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
@@ -200,17 +229,17 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // ---- LDS layout: K stages [4][64 rows][256 B] at 0, V stages at 64 KiB.  16-byte chunk c of K row r
   // sits at chunk c ^ (r & 15); chunk c of V row r at c ^ ((r & 3) << 2): both fragment reads below are
   // then bank-conflict free.  All per-lane addresses are fixed; stage and sub-block enter as immediates.
-  uint32_t kaddr[D / 16];   // A operand of QK: key row lq (+32), chunk 2 kk + half
+  uint32_t kaddr[8];   // A operand of QK: slot lq (+32), chunk 2 kk + half
 #pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) kaddr[kk] = lds0 + lq * kRowBytes + (((2 * kk + half) ^ (lq & 15)) << 4);
+  for (int kk = 0; kk < 8; ++kk) kaddr[kk] = lds0 + lq * kRowBytes + (((2 * kk + half) ^ (lq & 15)) << 4);
   // V^T fragments through the transposing read: within a 16-lane group lane s reads 4 consecutive d of key
   // row (s >> 2); the hardware hands lane i the 4 keys of d column i.
   const int grp = lane >> 4, gi = lane & 15;
   const int vt_row = 4 * (grp >> 1) + (gi >> 2);
   const int vt_dbyte = (16 * (grp & 1) + 4 * (gi & 3)) * 2;
-  uint32_t vaddr[D / 32];   // + 4096 ks (+ 2048 for keys +8), d block db
+  uint32_t vaddr[4];   // + 4096 ks (+ 2048 for slots +8), 64-byte block db of the slot
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
+  for (int db = 0; db < 4; ++db)
     vaddr[db] = lds0 + kVRegion + vt_row * kRowBytes + (((4 * db + (vt_dbyte >> 4)) ^ ((vt_row & 3) << 2)) << 4) + (vt_dbyte & 15);
 
   // ---- DMA loader: wavefront w moves rows 8w..8w+7 of every stage, 4 rows (1 KiB) per instruction; lane l
@@ -239,8 +268,16 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // per-lane walk
   RowCursor cur[2];
   uint32_t koff[2], voff[2];              // byte offsets from kh / vh of the next stage to issue
+  // head_dim 64: key (within a stage) whose chunk this lane moves, for K and for V
+  int ktok[2], vtok[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int slot_u = 8 * wave + 4 * u + ld_sub;
+    ktok[u] = 64 * (slot_u >> 5) + 32 * (int)(kchunk[u] >> 3) + (slot_u & 31);
+    vtok[u] = 64 * (slot_u >> 5) + 32 * (int)(vchunk[u] >> 3) + (slot_u & 31);
+  }
   if (MODE != kPerLane) {
-    const int n0 = 8 * wave;
+    const int n0 = (D == 128) ? 8 * wave : 0;
     const RowCursor c = cursor_at(vw, n0 < N ? n0 : 0);
     row_i = __builtin_amdgcn_readfirstlane(c.i);
     col_j = __builtin_amdgcn_readfirstlane(c.j);
@@ -249,8 +286,13 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     vcur += first;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      klane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + kchunk[u]) << 4;
-      vlane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + vchunk[u]) << 4;
+      if (D == 128) {
+        klane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + kchunk[u]) << 4;
+        vlane[u] = ((uint32_t)(4 * u + ld_sub) * vw.st16 + vchunk[u]) << 4;
+      } else {   // offsets from the stage's first key; the pointers below start at key 0, not at the wavefront's rows
+        klane[u] = ((uint32_t)ktok[u] * vw.st16 + (kchunk[u] & 7)) << 4;
+        vlane[u] = ((uint32_t)vtok[u] * vw.st16 + (vchunk[u] & 7)) << 4;
+      }
     }
   } else {
 #pragma unroll
@@ -261,13 +303,13 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
       voff[u] = (cur[u].off16 + vchunk[u]) << 4;
     }
   }
-  const uint64_t stage_bytes = (uint64_t)(kBC * 16) * vw.st16;
+  const uint64_t stage_bytes = (uint64_t)(kKeys * 16) * vw.st16;
   const uint64_t row_skip_bytes = (uint64_t)vw.row_skip16 << 4, frame_skip_bytes = (uint64_t)vw.frame_skip16 << 4;
-  auto scalar_advance = [&]() {   // the wavefront's rows move kBC tokens on
+  auto scalar_advance = [&]() SG_INLINE {   // the wavefront's rows move one stage on
     uint64_t delta = stage_bytes;
     if (MODE == kScalarWalk) {
-      col_j += kBC;
-      if (vw.tw >= kBC) {         // at most one tile-row wrap: branch-free
+      col_j += kKeys;
+      if (vw.tw >= kKeys) {         // at most one tile-row wrap: branch-free
         const bool wrap = col_j >= vw.tw;
         col_j -= wrap ? vw.tw : 0;
         row_i += wrap ? 1 : 0;
@@ -286,7 +328,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     vcur += delta;
   };
   // issue stage `blk` (all of its rows below N) into ring slot `st`; advance to the next stage
-  auto issue_full = [&](int blk, int st) {
+  auto issue_full = [&](int blk, int st) SG_INLINE {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       if (MODE != kPerLane) {
@@ -295,8 +337,8 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
       } else {
         dma16(kh, koff[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vh, voff[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-        const int n = blk * kBC + 8 * wave + 4 * u + ld_sub;
-        if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+        const int n = blk * kKeys + 8 * wave + 4 * u + ld_sub;
+        if (n + kKeys < N) cursor_advance(vw, cur[u], kKeys);
         koff[u] = (cur[u].off16 + kchunk[u]) << 4;
         voff[u] = (cur[u].off16 + vchunk[u]) << 4;
       }
@@ -304,12 +346,18 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     if (MODE != kPerLane) scalar_advance();
   };
   // same for a stage that may hold rows >= N: those lanes fetch the last valid row (masked later)
-  auto issue_any = [&](int blk, int st) {
-    const int n0 = blk * kBC + 8 * wave;   // wave-uniform
+  auto issue_any = [&](int blk, int st) SG_INLINE {
+    const int n0 = blk * kKeys + ((D == 128) ? 8 * wave : 0);   // wave-uniform
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int n = n0 + 4 * u + ld_sub;
-      if (MODE != kPerLane) {
+      if (D == 64) {               // the stage's first key is valid; keys >= N take the last row, at or after it
+        const uint32_t back = (uint32_t)(((const char*)kh + ((uint64_t)last16 << 4)) - kcur);
+        const uint32_t ko = (n0 + ktok[u] < N) ? klane[u] : back + ((kchunk[u] & 7) << 4);
+        const uint32_t vo = (n0 + vtok[u] < N) ? vlane[u] : back + ((vchunk[u] & 7) << 4);
+        dma16(kcur, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
+        dma16(vcur, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
+      } else if (MODE != kPerLane) {
         if (n0 + 7 < N) {          // all 8 rows valid
           dma16(kcur, klane[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
           dma16(vcur, vlane[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
@@ -329,12 +377,12 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
         const uint32_t vo = (n < N) ? voff[u] : ((last16 + vchunk[u]) << 4);
         dma16(kh, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vh, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-        if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+        if (n + kKeys < N) cursor_advance(vw, cur[u], kKeys);
         koff[u] = (cur[u].off16 + kchunk[u]) << 4;
         voff[u] = (cur[u].off16 + vchunk[u]) << 4;
       }
     }
-    if (MODE != kPerLane && n0 + kBC < N) scalar_advance();
+    if (MODE != kPerLane && n0 + kKeys < N) scalar_advance();
   };
 
   f32x16 oacc[D / 32];
@@ -349,10 +397,10 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 #pragma unroll
   for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
 
-  auto kfrag = [&](int kk, int kb, int off) -> bf16x8 {
+  auto kfrag = [&](int kk, int kb, int off) SG_INLINE -> bf16x8 {
     return __builtin_bit_cast(bf16x8, *(const SG_LDS u32x4*)(uintptr_t)(kaddr[kk] + off + kb * (32 * kRowBytes)));
   };
-  auto vfrag = [&](int ks, int db, int off) -> bf16x8 {
+  auto vfrag = [&](int ks, int db, int off) SG_INLINE -> bf16x8 {
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(uintptr_t)(vaddr[db] + off + ks * (16 * kRowBytes)));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SG_LDS s16x4*)(uintptr_t)(vaddr[db] + off + ks * (16 * kRowBytes) + 8 * kRowBytes));
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -366,30 +414,39 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   constexpr int kKPre = 1;
   bf16x8 kpre[kKPre][2];  // K fragments of the first kKPre QK steps, read during the PV tail
   // S^T = K Q^T of the stage at LDS byte offset `off`: two independent accumulator chains
-  auto qk = [&](int off, f32x16 (&s)[2], bool prefetched) {
-    bf16x8 a[D / 16][2];
+  // head_dim 64: the second half of a slot is another key, so steps kk >= 4 feed the next score block
+  // (block 2 kb + (kk >> 2), Q fragment kk & 3) and there are four chains, two of them in flight at a time
+  auto qk = [&](int off, f32x16 (&s)[kMaxSB], bool prefetched) SG_INLINE {
+    bf16x8 a[8][2];
 #pragma unroll
     for (int kk = 0; kk < kPF; ++kk) {
       if (prefetched && kk < kKPre) { a[kk][0] = kpre[kk][0]; a[kk][1] = kpre[kk][1]; }
       else { a[kk][0] = kfrag(kk, 0, off); a[kk][1] = kfrag(kk, 1, off); }
     }
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      if (kk + kPF < D / 16) { a[kk + kPF][0] = kfrag(kk + kPF, 0, off); a[kk + kPF][1] = kfrag(kk + kPF, 1, off); }
+    for (int kk = 0; kk < 8; ++kk) {
+      if (kk + kPF < 8) { a[kk + kPF][0] = kfrag(kk + kPF, 0, off); a[kk + kPF][1] = kfrag(kk + kPF, 1, off); }
       __builtin_amdgcn_sched_barrier(0);
-      if (kk == 0) {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[kk], cinit, 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[kk], cinit, 0, 0, 0);
+      constexpr int kPerChain = D / 16;            // MFMA steps per score block
+      const int b0 = (D == 128) ? 0 : (kk >> 2);   // score blocks fed by this step: b0 and b0 + kSB / 2
+      const int b1 = b0 + kSB / 2;
+      const int qi = kk % kPerChain;
+      if (qi == 0) {
+        s[b0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[qi], cinit, 0, 0, 0);
+        s[b1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[qi], cinit, 0, 0, 0);
       } else {
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[kk], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[kk], s[1], 0, 0, 0);
+        s[b0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][0], qf[qi], s[b0], 0, 0, 0);
+        s[b1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk][1], qf[qi], s[b1], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   // O^T += V^T P^T: four independent accumulator chains (one per 32 rows of d); if a QK product follows
   // (K stage at `k_off`), its first fragments are read in the last step
-  auto pv = [&](int off, const bf16x8 (&pp)[4], int k_off, bool k_follows) {
+  // (head_dim 64: fragment (ks, db) is d block db & 1 of the 16 keys 4 (ks >> 1) + 2 (db >> 1) + (ks & 1), two chains)
+  auto pv = [&](int off, const bf16x8 (&pp)[2 * kMaxSB], int k_off, bool k_follows) SG_INLINE {
+    auto acc_of = [](int i) SG_INLINE { return (D == 128) ? (i & 3) : (i & 1); };
+    auto p_of = [](int i) SG_INLINE { return (D == 128) ? (i >> 2) : 4 * (i >> 3) + 2 * ((i & 3) >> 1) + ((i >> 2) & 1); };
     bf16x8 a[16];
 #pragma unroll
     for (int i = 0; i < 2 * kPF; ++i) a[i] = vfrag(i >> 2, i & 3, off);
@@ -404,28 +461,28 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
         kpre[kk][1] = kfrag(kk, 1, k_off);
       }
       __builtin_amdgcn_sched_barrier(0);
-      oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], pp[i >> 2], oacc[i & 3], 0, 0, 0);
-      oacc[(i + 1) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i + 1], pp[(i + 1) >> 2], oacc[(i + 1) & 3], 0, 0, 0);
+      oacc[acc_of(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], pp[p_of(i)], oacc[acc_of(i)], 0, 0, 0);
+      oacc[acc_of(i + 1)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i + 1], pp[p_of(i + 1)], oacc[acc_of(i + 1)], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  f32x16 s[2];   // scores of the stage in flight between an MFMA phase and the next softmax phase
+  f32x16 s[kMaxSB];   // scores of the stage in flight (the first kSB entries) between an MFMA phase and the next softmax phase
   // softmax phase of one stage: scores t (exponent domain) -> p, l.  The exponentials are taken against the
   // current reference; if one of them outgrew the guard (or on the first stage, which sets the reference) the
   // reference moves by delta per query: scores, running sum and output accumulators are brought to the new
   // reference and the exponentials are retaken.  One copy of the code, looped at most twice.
-  auto softmax_phase = [&](int key0, bool masked, bool first, bf16x8 (&p)[4]) {
-    if (masked) mask_tail(s, key0, N);
+  auto softmax_phase = [&](int key0, bool masked, bool first, bf16x8 (&p)[2 * kMaxSB]) SG_INLINE {
+    if (masked) mask_tail<kSB>(s, key0, N);
     bool move = first;
     float sum;
 #pragma nounroll
     for (;;) {
       if (move) {
-        const float mx = block_max(s);
+        const float mx = block_max<kSB>(s);
         const float delta = first ? mx : fmaxf(mx, 0.f);
         const float alpha = first ? 0.f : __builtin_amdgcn_exp2f(-delta);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) s[kb] -= delta;
+        for (int kb = 0; kb < kSB; ++kb) s[kb] -= delta;
         sm.M += delta;
 #pragma unroll
         for (int r = 0; r < 16; ++r) cinit[r] = -sm.M;
@@ -433,7 +490,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) oacc[db] *= alpha;
       }
-      sum = exp_block(s, p);
+      sum = exp_block<kSB>(s, p);
       if (move || !__any(!(sum < kOverflowGuard))) break;
       move = true;
     }
@@ -447,38 +504,46 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // starts softmax k followed by MFMA phase k.
   // Ring of 4 stages: between B_k and B_k+1 both groups read V of stage k and K of stage k+1; stage k+3 is
   // issued right after B_k into the slot of stage k-1 (last read before B_k) and must have landed by B_k+2.
-  const int n_blocks = (N + kBC - 1) / kBC;
-  const bool tail = (N % kBC) != 0;
+  const int n_blocks = (N + kKeys - 1) / kKeys;
+  const bool tail = (N % kKeys) != 0;
   const int grp1 = __builtin_amdgcn_readfirstlane(wave >> 2);
-  auto wait_stage = [&](int younger_stages) {   // own transfers: all but the youngest `younger_stages` stages landed
+  auto wait_stage = [&](int younger_stages) SG_INLINE {   // own transfers: all but the youngest `younger_stages` stages landed
     __builtin_amdgcn_sched_barrier(0);
     if (younger_stages >= 2) wait_vmcnt<8>();
     else if (younger_stages == 1) wait_vmcnt<4>();
     else wait_vmcnt<0>();
   };
-  bf16x8 p[4];
-  auto mfma_phase_static = [&](auto st_tag) {
+  bf16x8 p[2 * kMaxSB];   // the first 2 kSB entries
+  // keeps the score registers live across the phase boundary (a macro: the statement has to sit in the
+  // lambdas that are its call sites)
+#define SG_PIN_SCORES()                                                                \
+  do {                                                                                 \
+    asm volatile("" : : "v"(s[0]), "v"(s[1]));                                         \
+    if constexpr (kSB == 4) asm volatile("" : : "v"(s[kSB - 2]), "v"(s[kSB - 1]));      \
+  } while (0)
+  auto mfma_phase_static = [&](auto st_tag) SG_INLINE {
     constexpr int ST = decltype(st_tag)::value;
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
     pv(ST * kTileBytes, p, ((ST + 1) % kStages) * kTileBytes, true);
     qk(((ST + 1) % kStages) * kTileBytes, s, true);
-    asm volatile("" : : "v"(s[0]), "v"(s[1]));
+    SG_PIN_SCORES();
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto mfma_phase_any = [&](int k) {
+  auto mfma_phase_any = [&](int k) SG_INLINE {
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
     pv((k % kStages) * kTileBytes, p, ((k + 1) % kStages) * kTileBytes, k + 1 < n_blocks);
     if (k + 1 < n_blocks) qk(((k + 1) % kStages) * kTileBytes, s, true);
-    asm volatile("" : : "v"(s[0]), "v"(s[1]));
+    SG_PIN_SCORES();
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto softmax_pinned = [&](int j, bool masked, bool first) {
-    softmax_phase(j * kBC, masked, first, p);
+  auto softmax_pinned = [&](int j, bool masked, bool first) SG_INLINE {
+    softmax_phase(j * kKeys, masked, first, p);
     asm volatile("" : : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(sm.l), "v"(cinit));
+    if constexpr (kSB == 4) asm volatile("" : : "v"(p[kSB]), "v"(p[kSB + 1]), "v"(p[kSB + 2]), "v"(p[kSB + 3]));
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -487,21 +552,21 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   wait_stage(n_blocks >= 3 ? 2 : (n_blocks == 2 ? 1 : 0));
   meet();
   qk(0, s, false);
-  asm volatile("" : : "v"(s[0]), "v"(s[1]));
+  SG_PIN_SCORES();
   const int n_steady = (n_blocks >= 2 * kStages) ? kStages + ((n_blocks - 2 * kStages) / kStages) * kStages : 0;
 
   if (!grp1) {
     softmax_pinned(0, tail && n_blocks == 1, true);
     wait_stage(n_blocks >= 3 ? 1 : 0);
     meet();   // B_0
-    auto general = [&](int k) {
+    auto general = [&](int k) SG_INLINE {
       if (k + 3 < n_blocks) issue_any(k + 3, (k + 3) % kStages);
       mfma_phase_any(k);
       if (k + 1 < n_blocks) softmax_pinned(k + 1, tail && k + 1 == n_blocks - 1, false);
       wait_stage(k + 3 <= n_blocks - 1 ? 1 : 0);
       meet();
     };
-    auto steady = [&](int k, auto st_tag) {
+    auto steady = [&](int k, auto st_tag) SG_INLINE {
       constexpr int ST = decltype(st_tag)::value;
       issue_full(k + 3, (ST + 3) % kStages);
       mfma_phase_static(st_tag);
@@ -521,14 +586,14 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   } else {
     wait_stage(n_blocks >= 3 ? 1 : 0);
     meet();   // B_0
-    auto general = [&](int k) {
+    auto general = [&](int k) SG_INLINE {
       if (k + 3 < n_blocks) issue_any(k + 3, (k + 3) % kStages);
       softmax_pinned(k, tail && k == n_blocks - 1, k == 0);
       mfma_phase_any(k);
       wait_stage(k + 3 <= n_blocks - 1 ? 1 : 0);
       meet();
     };
-    auto steady = [&](int k, auto st_tag) {
+    auto steady = [&](int k, auto st_tag) SG_INLINE {
       constexpr int ST = decltype(st_tag)::value;
       issue_full(k + 3, (ST + 3) % kStages);
       softmax_pinned(k, false, false);
@@ -573,10 +638,11 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 
 int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
                           const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
-  // head_dim 64 (half-length rows) is served by the register-staged kernel; the streaming kernel below is
-  // laid out for 256-byte rows
-  if (head_dim == 64) return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
-  if (head_dim != 128) return SG_ERR_UNSUPPORTED;
+  if (head_dim != 128 && head_dim != 64) return SG_ERR_UNSUPPORTED;
+  // head_dim 64 streams packed tiles only (two keys share an LDS slot, 32 keys apart: not one tile row);
+  // tiles read in place from a canvas take the register-staged kernel
+  if (head_dim == 64 && !(tv.W == tv.tw && tv.H == tv.th))
+    return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
   View16 vw;
   vw.base16 = (uint32_t)(tv.base / 8);
   vw.st16 = (uint32_t)(tv.stride_token / 8);
@@ -600,7 +666,7 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   dim3 grid(per_xcd * kXcd);
   // the kernels need more dynamic LDS than the default limit; the attribute is set once per device and kernel
   constexpr int kMaxDevices = 64;
-  static bool attr_set[kMaxDevices][3] = {};
+  static bool attr_set[kMaxDevices][4] = {};
   int dev = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   auto launch = [&](auto kern, int slot) -> int {
@@ -613,7 +679,8 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
     return SG_OK;
   };
   int st = SG_OK;
-  if (mode == kLinear) st = launch(attention_bf16_kernel<128, kLinear>, kLinear);
+  if (head_dim == 64) st = launch(attention_bf16_kernel<64, kLinear>, 3);
+  else if (mode == kLinear) st = launch(attention_bf16_kernel<128, kLinear>, kLinear);
   else if (mode == kScalarWalk) st = launch(attention_bf16_kernel<128, kScalarWalk>, kScalarWalk);
   else st = launch(attention_bf16_kernel<128, kPerLane>, kPerLane);
   if (st != SG_OK) return st;

@@ -85,6 +85,17 @@ def test_attention_bf16_head_dim_64(case):
         assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, tr, tc), "bf16", f"{name} {tr},{tc}")
 
 
+@pytest.mark.parametrize("shape", [(3, 20, 25), (2, 33, 37), (4, 16, 32)], ids=["n1500", "n2442", "n2048"])
+def test_attention_bf16_head_dim_64_long_packed(shape):
+    """Packed head_dim-64 tiles long enough for the steady loop of the streaming kernel (128-key stages,
+    two keys per LDS slot): 11.7, 19.1 and exactly 16 stages."""
+    T, H, W = shape
+    g = _geom("d64long", T, H, W, H, W, H, W, 2, 64, "bf16", 27)
+    q, k, v = canvas_qkv(g)
+    got = gpu_tile_attention(g, q, k, v, 0, 0)
+    assert_close(to_f64(got), oracle_tile_attention_full(g, q, k, v, 0, 0), "bf16")
+
+
 def test_step_bf16_head_dim_64():
     g = _geom("d64step", 2, 14, 20, 8, 12, 6, 8, 3, 64, "bf16", 25)
     q, k, v = canvas_qkv(g)
