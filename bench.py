@@ -268,8 +268,19 @@ def other_configs(torch, sg, args):
 
 def full_extras(torch, sg, args, kept):
     """Inter-step cache policy figures at the 4K sizes: the refresh pass, ten steps through sg_refine_step, tile std."""
-    from synthetic import perturb_, randn_tensor
+    from dataclasses import replace
+    from synthetic import perturb_, randn_tensor, CONFIGS
     res = {}
+    # the 720p tile at the head shape of CogVideoX-1.5 (48 heads x 64, Section 8 "Workloads"): packed head_dim-64 path
+    g64 = replace(CONFIGS["tile720p_bf16"], heads=48, head_dim=64)
+    p64 = sg.make_problem(g64)
+    x64 = [torch.randn(g64.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    o64 = torch.empty(g64.tile_shape, dtype=torch.bfloat16, device="cuda")
+    ms64 = time_calls(torch, lambda: sg.sg_tile_attention(p64, x64[0], x64[1], x64[2], 0, 0, o64), 5)
+    fl64 = 4.0 * g64.tile_tokens ** 2 * 64 * 48
+    res["attention_tile720p_48x64"] = {"ms": round(ms64, 3), "TFLOP/s": round(fl64 / ms64 * 1e-9, 1),
+                                       "frac_bf16_peak": round(fl64 / ms64 * 1e-9 / PEAK_BF16_TFLOPS, 4)}
+    del x64, o64
     g5, p5, n5, cache_out, scores, rec, ws, canvas, eps = (kept[k] for k in ("g5", "p5", "n5", "cache_out", "scores", "rec", "ws", "canvas", "eps"))
     tile_x = cache_x = None
     kept.pop("tile_x"); kept.pop("cache_x")
