@@ -58,6 +58,18 @@ def test_config2_single_720p_tile():
     assert 0.7 * (np.e / g.tile_tokens) ** 0.5 < rms < 1.4 * (np.e / g.tile_tokens) ** 0.5
 
 
+def test_720p_tile_at_48_heads_of_64():
+    """The same tile at the head shape of CogVideoX-1.5 (Section 8 "Workloads"): the packed head_dim-64 path."""
+    from dataclasses import replace
+    g = replace(CONFIGS["tile720p_bf16"], name="tile720p_48x64", heads=48, head_dim=64, seed=1064)
+    qkv = _device_canvas(g)
+    out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
+    sg.sg_tile_attention(sg.make_problem(g), *qkv, 0, 0, out)
+    torch.cuda.synchronize()
+    worst, rel = _check_tile(g, qkv, 0, 0, out, [0, 17, 47], 96, g.seed)
+    print(f"48 x 64: 288 sampled rows max_abs={worst:.3e} rel_l2={rel:.3e}")
+
+
 def _blend_plane_check(g, tiles, canvas, planes):
     """Whole (head, frame) planes of the canvas against the oracle blend of the same GPU tile outputs."""
     from dataclasses import replace
