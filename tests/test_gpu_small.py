@@ -59,6 +59,8 @@ BF16_CASES = [
     ("view_3x3", 2, 20, 40, 12, 24, 4, 8, 2),           # N = 576, triple row coverage; tile width 24: scalar walk, several row wraps per stage
     ("view_w72", 2, 8, 136, 6, 72, 2, 64, 2),           # N = 864, tile width 72 >= one stage: scalar walk, at most one wrap per stage
     ("view_w8", 3, 40, 12, 32, 8, 8, 4, 1),             # N = 768, tile width 8: eight row wraps per stage, frame wraps
+    ("view_w3", 7, 9, 5, 5, 3, 4, 2, 2),                # N = 105, tile width 3: per-lane cursors wrap many rows and frames per stage
+    ("view_w1", 9, 4, 3, 4, 1, 4, 1, 1),                # N = 36, tile width 1: every token is its own tile row
 ]
 
 
