@@ -152,7 +152,7 @@ int sg_tile_slice(const sg_problem* p, const void* const* src, int32_t n_src, in
  *     recompute[i] = !has_cache[i] || score[i] >= threshold
  * A tile without a cache gets score +inf and its buffers are not read.
  *   x_cur, x_cached  host arrays of n_tiles device pointers, each `elems_per_tile` elements of
- *                    `dtype`, 16-byte aligned; elems_per_tile must be a multiple of 8
+ *                    `dtype`, 16-byte aligned; any elems_per_tile >= 0 (a ragged tail is summed too)
  *   has_cache        device, n_tiles bytes (0/1)
  *   scores           device, n_tiles floats (out);  recompute: device, n_tiles bytes (out)
  *   workspace        device scratch of at least sg_workspace_bytes(n_tiles)
