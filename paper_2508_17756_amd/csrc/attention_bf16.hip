@@ -22,6 +22,7 @@
 //
 // Built with -fno-honor-nans: a NaN in Q, K or V gives unspecified (not necessarily NaN) output.
 #include <type_traits>
+#include <atomic>
 #include "sg_common.h"
 
 namespace sg {
@@ -666,13 +667,13 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   dim3 grid(per_xcd * kXcd);
   // the kernels need more dynamic LDS than the default limit; the attribute is set once per device and kernel
   constexpr int kMaxDevices = 64;
-  static bool attr_set[kMaxDevices][4] = {};
+  static std::atomic<bool> attr_set[kMaxDevices][4];   // zero-initialised; set twice by racing threads is harmless
   int dev = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   auto launch = [&](auto kern, int slot) -> int {
-    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot]) {
+    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
       SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-      if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot] = true;
+      if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
     }
     kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
                                            (const u32x4*)v, (uint16_t*)out, run_flag);

@@ -5,6 +5,7 @@
 // and values staged through LDS and read back as wave-wide broadcasts, softmax in the online
 // (running max / running sum) form, which is algebraically the two-pass softmax.  The four
 // partial states (m, l, o) of a query are merged through LDS at the end.
+#include <atomic>
 #include "sg_common.h"
 
 namespace sg {
@@ -156,14 +157,14 @@ int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scal
   const size_t lds = ((size_t)2 * kSplit * kKC * head_dim + 2 * kSplit * kQ) * sizeof(float);
   static_assert(2 * kKC == kQ, "the merge buffer is sized by the chunk buffers");
   constexpr int kMaxDevices = 64;
-  static bool attr_set[kMaxDevices][2] = {};
+  static std::atomic<bool> attr_set[kMaxDevices][2];   // zero-initialised; set twice by racing threads is harmless
   int dev = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
   const int slot = head_dim == 64 ? 0 : 1;
   const void* kern = head_dim == 64 ? (const void*)attention_f32_kernel<64> : (const void*)attention_f32_kernel<128>;
-  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot]) {
+  if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
     SG_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot] = true;
+    if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
   }
   if (head_dim == 64) attention_f32_kernel<64><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
   else attention_f32_kernel<128><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
