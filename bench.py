@@ -196,10 +196,21 @@ def cpu_baseline_streaming(torch, seed=7):
     t0 = time.perf_counter()
     oracle.blend(tiles, g)
     t_blend = time.perf_counter() - t0
+    # the whole tiny configuration through the oracle: 4 tile attentions and the blend
+    q, k, v = (rng.standard_normal(g.grid_shape) for _ in range(3))
+    t0 = time.perf_counter()
+    outs = []
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            o = oracle.tile_attention(q, k, v, g, tr, tc, g.scale)
+            outs.append(np.stack([o[a] for a in range(g.heads)]).reshape(g.tile_shape))
+    oracle.blend(outs, g)
+    t_cfg1 = time.perf_counter() - t0
     elems = g.n_tiles * int(np.prod(g.tile_shape)) + int(np.prod(g.grid_shape))
     return {"gate_elements_per_s": round(2 * n / t_gate, 1), "gate_sample": "2 x %d fp64 values, %.2f s" % (n, t_gate),
             "blend_elements_per_s": round(elems / t_blend, 1),
-            "blend_sample": "config 1 (4 tiles -> 3x16x16 grid, 2 heads x 64), %.4f s" % t_blend}
+            "blend_sample": "config 1 (4 tiles -> 3x16x16 grid, 2 heads x 64), %.4f s" % t_blend,
+            "config1_full_step_s": round(t_cfg1, 4)}
 
 
 def other_configs(torch, sg, args):
