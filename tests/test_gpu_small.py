@@ -108,14 +108,15 @@ def test_step_bf16_head_dim_64():
     assert_close(to_f64(canvas), oracle.blend(ref, g), "bf16")
 
 
-def test_attention_bf16_token_major_layout():
-    """[T][H][W][heads][d] canvas through the stride fields."""
-    g = _geom("tokmaj", 2, 12, 18, 8, 10, 4, 8, 3, 128, "bf16", 31)
+@pytest.mark.parametrize("dtype,d,tw", [("bf16", 128, 10), ("bf16", 128, 16), ("bf16", 64, 10), ("f32", 64, 10), ("f32", 128, 10)])
+def test_attention_token_major_layout(dtype, d, tw):
+    """[T][H][W][heads][d] canvas through the stride fields, every kernel (tile width 16: scalar walk)."""
+    g = _geom("tokmaj", 2, 12, tw + 8, 8, tw, 4, 8, 3, d, dtype, 31)
     qkv_hm = canvas_qkv(g)
     qkv_tm = [t.permute(1, 2, 3, 0, 4).contiguous() for t in qkv_hm]
-    out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(g.tile_shape, dtype=torch_dtype(dtype), device="cuda")
     sg.sg_tile_attention(sg.make_problem(g, token_major=True), *qkv_tm, 1, 1, out)
-    assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv_hm, 1, 1), "bf16")
+    assert_close(to_f64(out), oracle_tile_attention_full(g, *qkv_hm, 1, 1), dtype)
 
 
 @pytest.mark.parametrize("tw", [20, 24], ids=["per_lane_rows", "scalar_walk"])
