@@ -290,8 +290,9 @@ def test_step_canvas_mode_tiny_f32():
     assert_close(to_f64(canvas), oracle.blend(outs, g), "f32")
 
 
-def test_step_cached_mode_bf16_three_steps():
-    g = _geom("stepc", 2, 14, 20, 8, 12, 6, 8, 2, 128, "bf16", 61)       # 2x2 tiles, N = 192
+@pytest.mark.parametrize("d", [128, 64])
+def test_step_cached_mode_bf16_three_steps(d):
+    g = _geom("stepc", 2, 14, 20, 8, 12, 6, 8, 2, d, "bf16", 61)         # 2x2 tiles, N = 192
     n = g.n_tiles
     canvas_in = canvas_qkv(g)
     tile_x = []
