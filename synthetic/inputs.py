@@ -5,20 +5,21 @@ and on the device for the full-size ones; the stored values are the ground
 truth both sides read.
 """
 import numpy as np
-import torch
 
-_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+# torch is imported where it is used: the geometry-only users of this package do not pay for it
 
 
 def torch_dtype(name):
-    return _DT[name]
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
 
 
 def randn_tensor(shape, dtype, seed, device="cpu"):
     """i.i.d. N(0, 1) values of the given dtype ("f32" | "bf16"), seeded."""
+    import torch
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
-    return torch.randn(tuple(shape), dtype=_DT[dtype], device=device, generator=gen)
+    return torch.randn(tuple(shape), dtype=torch_dtype(dtype), device=device, generator=gen)
 
 
 def eps_table(seed, steps, n_tiles, choices=(0.01, 0.1)):
@@ -32,6 +33,7 @@ def eps_table(seed, steps, n_tiles, choices=(0.01, 0.1)):
 def perturb_(x, eps, seed, chunk=1 << 26):
     """In place x <- round_to_dtype(float32(x) + eps * n), n ~ N(0, 1) in fp32.
     The next denoising step's tile input of the gated workload."""
+    import torch
     gen = torch.Generator(device=x.device)
     gen.manual_seed(int(seed))
     flat = x.view(-1)
