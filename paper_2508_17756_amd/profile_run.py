@@ -9,6 +9,7 @@ Sections (choose with --kernels, comma separated):
   copy       an elementwise copy of a 2 GiB buffer (reads 2 GiB, writes 2 GiB): the known
              traffic the FETCH_SIZE / WRITE_SIZE counters are scaled by
   attention  sg_tile_attention on the 75,600-token tile, 40 heads x 128, bf16
+  attention64  the same tile at 48 heads x 64 (not in the default list)
   blend      sg_tile_blend of the 4K canvas (20 tiles of 75,600 tokens -> 21 x 135 x 240)
   gate       sg_cache_gate over 4 tiles of packed Q,K,V (2.32 GB per tile and side)
   update     sg_tile_blend_update of the 4K canvas (blend + scheduler update in place)
@@ -66,6 +67,18 @@ def main():
         E = int(np.prod(g.tile_shape))
         say("attention: %d launches, %.6e FLOP per launch, algorithmic HBM bytes per launch %d (Q,K,V read once, O written once)"
             % (args.reps, g.attention_flops_per_tile, 4 * E * 2))
+        del q, k, v, out
+
+    if "attention64" in todo:
+        from dataclasses import replace
+        g = replace(CONFIGS["tile720p_bf16"], heads=48, head_dim=64)
+        p = sg.make_problem(g)
+        q, k, v = (torch.randn(g.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
+        for _ in range(args.reps):
+            sg.sg_tile_attention(p, q, k, v, 0, 0, out)
+        torch.cuda.synchronize()
+        say("attention64: %d launches, %.6e FLOP per launch (48 heads x 64)" % (args.reps, 4.0 * g.tile_tokens ** 2 * 64 * 48))
         del q, k, v, out
 
     if "blend" in todo:
