@@ -154,21 +154,22 @@ def test_attention_bf16_large_logits_and_constant_v():
     assert float((got.float() - 0.75).abs().max()) <= 0.75 * 2 ** -7
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("order", ["ascending", "descending", "spike"])
-def test_attention_bf16_softmax_reference_moves(order):
+def test_attention_bf16_softmax_reference_moves(order, d):
     """Scores that keep growing along the key axis (the running reference must move again and again),
     that start at their maximum, or that hold one huge outlier: same numbers as the two-pass oracle."""
-    g = _geom("adv", 2, 12, 16, 12, 16, 12, 16, 2, 128, "bf16", 43)       # N = 384 = 6 stages
+    g = _geom("adv", 2, 12, 16, 12, 16, 12, 16, 2, d, "bf16", 43)         # N = 384 = 6 stages (3 at head_dim 64)
     q, k, v = canvas_qkv(g)
     N = g.tile_tokens
-    u = torch.nn.functional.normalize(randn_tensor((128,), "f32", 5).cuda(), dim=0)
+    u = torch.nn.functional.normalize(randn_tensor((d,), "f32", 5).cuda(), dim=0)
     ramp = torch.linspace(0.0, 1.0, N, device="cuda")
     if order == "descending":
         ramp = ramp.flip(0)
     if order == "spike":
         ramp = torch.zeros(N, device="cuda")
         ramp[N // 2 + 7] = 1.0
-    # q along u with length 30; keys get up to 40 u: logits (scale 1/sqrt(128)) span ~0 .. 106, i.e. 150 in log2
+    # q along u with length 30; keys get up to 40 u: logits (scale 1/sqrt(d)) span ~0 .. 106 (150 at head_dim 64), far beyond 2^16
     q = (q.float() * 0.3 + 30.0 * u).to(torch.bfloat16)
     k = (k.float() * 0.3 + (40.0 * ramp).reshape(1, g.T, g.tile_h, g.tile_w, 1) * u).to(torch.bfloat16)
     got = gpu_tile_attention(g, q, k, v, 0, 0)
