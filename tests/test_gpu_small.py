@@ -155,11 +155,13 @@ def test_attention_bf16_large_logits_and_constant_v():
 
 
 @pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("frames", [2, 11], ids=["n384", "n2112"])
 @pytest.mark.parametrize("order", ["ascending", "descending", "spike"])
-def test_attention_bf16_softmax_reference_moves(order, d):
+def test_attention_bf16_softmax_reference_moves(order, frames, d):
     """Scores that keep growing along the key axis (the running reference must move again and again),
-    that start at their maximum, or that hold one huge outlier: same numbers as the two-pass oracle."""
-    g = _geom("adv", 2, 12, 16, 12, 16, 12, 16, 2, d, "bf16", 43)         # N = 384 = 6 stages (3 at head_dim 64)
+    that start at their maximum, or that hold one huge outlier: same numbers as the two-pass oracle.
+    N = 384 stays in the kernel's first stages, N = 2112 moves the reference inside its steady loop."""
+    g = _geom("adv", frames, 12, 16, 12, 16, 12, 16, 2, d, "bf16", 43)
     q, k, v = canvas_qkv(g)
     N = g.tile_tokens
     u = torch.nn.functional.normalize(randn_tensor((d,), "f32", 5).cuda(), dim=0)
