@@ -507,7 +507,12 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // issued right after B_k into the slot of stage k-1 (last read before B_k) and must have landed by B_k+2.
   const int n_blocks = (N + kKeys - 1) / kKeys;
   const bool tail = (N % kKeys) != 0;
-  const int grp1 = __builtin_amdgcn_readfirstlane(wave >> 2);
+  // Which wavefront of a SIMD takes which role matters: the SIMD serves its older wavefront (0-3) first.  With
+  // head_dim 128 (MFMA phase longer than the softmax phase) the older one leads with the MFMA phase; with head_dim 64
+  // (softmax phase longer) it has to lead with the softmax, or the younger one's softmax starves behind both phases of
+  // the older one and its MFMA phase then runs with nothing beside it (measured: 1.08 -> 1.22 PFLOP/s; the opposite
+  // choice costs head_dim 128 a quarter of its rate).
+  const int grp1 = __builtin_amdgcn_readfirstlane((wave >> 2) ^ (D == 64 ? 1 : 0));
   auto wait_stage = [&](int younger_stages) SG_INLINE {   // own transfers: all but the youngest `younger_stages` stages landed
     __builtin_amdgcn_sched_barrier(0);
     if (younger_stages >= 2) wait_vmcnt<8>();
