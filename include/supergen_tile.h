@@ -17,7 +17,8 @@
  * Conventions shared by every entry point
  *   - "device" pointers are HIP device memory on the current device; "host" pointers are
  *     ordinary process memory.  Every buffer is owned by the caller; the library allocates
- *     nothing and keeps no state between calls (scratch comes from the caller's workspace).
+ *     nothing and keeps no state between calls (scratch comes from the caller's workspace;
+ *     sg_cache_gate_static alone uses a fixed device array of the library's own).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it and the calls return without waiting; no host readback takes place.
  *   - Every call is a fixed sequence of kernel launches, so it can be captured in a HIP graph and
@@ -163,6 +164,22 @@ int sg_cache_gate(const void* const* x_cur, const void* const* x_cached, const u
                   int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float threshold,
                   float* scores, uint8_t* recompute, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/*
+ * sg_cache_gate for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * sg_cache_gate, but without a workspace: the partial sums live in a fixed 1 MiB device array inside
+ * the library (one copy per device, held until the process ends).  The call allocates and frees
+ * nothing.  At most SG_STATIC_GATE_MAX_TILES tiles per call; more returns SG_ERR_WORKSPACE and
+ * launches nothing.  Every call on a device shares that device's array: calls that may overlap on one
+ * device (different streams, different threads) race and must be ordered by the caller; calls on one
+ * stream are ordered by the stream.  Nothing needs clearing between calls.  The first call on a
+ * device looks the array's address up; make it outside of graph capture.
+ */
+#define SG_STATIC_GATE_MAX_TILES 64
+int sg_cache_gate_static(const void* const* x_cur, const void* const* x_cached, const uint8_t* has_cache,
+                         int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float threshold,
+                         float* scores, uint8_t* recompute, void* stream);
 
 /* Buffers of one tiled step.  All arrays of pointers are host arrays of device pointers. */
 typedef struct sg_step_io {

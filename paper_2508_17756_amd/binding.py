@@ -11,6 +11,7 @@ import os
 SG_F32, SG_BF16 = 0, 1
 SG_OK, SG_ERR_INVALID_ARG, SG_ERR_UNSUPPORTED, SG_ERR_WORKSPACE, SG_ERR_HIP = 0, -1, -2, -3, -4
 SG_REGION_MAXMIN, SG_REGION_TOPSELECT = 0, 1
+SG_STATIC_GATE_MAX_TILES = 64
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -112,6 +113,8 @@ def load_library():
     lib.sg_tile_slice.argtypes = [ctypes.POINTER(sg_problem), pp, i32, i32, i32, vp, vp]
     lib.sg_cache_gate.restype = ctypes.c_int
     lib.sg_cache_gate.argtypes = [pp, pp, vp, i32, i64, i32, f32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.sg_cache_gate_static.restype = ctypes.c_int
+    lib.sg_cache_gate_static.argtypes = [pp, pp, vp, i32, i64, i32, f32, vp, vp, vp]
     lib.sg_denoise_step_tiled.restype = ctypes.c_int
     lib.sg_denoise_step_tiled.argtypes = [ctypes.POINTER(sg_problem), ctypes.POINTER(sg_step_io), vp]
     lib.sg_gain_gate.restype = ctypes.c_int
@@ -246,6 +249,17 @@ def sg_cache_gate(x_cur, x_cached, has_cache, threshold, scores, recompute, work
                                       workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                       _stream())
     _check(st, "sg_cache_gate")
+    return scores, recompute
+
+
+def sg_cache_gate_static(x_cur, x_cached, has_cache, threshold, scores, recompute, elems_per_tile=None):
+    """sg_cache_gate without a workspace (the library's fixed scratch; at most SG_STATIC_GATE_MAX_TILES tiles)."""
+    n = len(x_cur)
+    elems = int(elems_per_tile if elems_per_tile is not None else (x_cur[0].numel() if n else 0))
+    dt = _dtype_code(x_cur[0]) if n else SG_BF16
+    st = load_library().sg_cache_gate_static(_ptr_array(x_cur), _ptr_array(x_cached), _ptr(has_cache), n, elems, dt,
+                                             float(threshold), _ptr(scores), _ptr(recompute), _stream())
+    _check(st, "sg_cache_gate_static")
     return scores, recompute
 
 
