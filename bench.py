@@ -10,9 +10,11 @@ skipped.  `value` = attention FLOPs (4 N^2 d heads, true N) / step time.
 
 Prints ONE JSON line.  Extra objects: `roofline` (the attention kernel alone, timed with HIP
 events on its stream; `traffic` = HBM bytes per launch from the committed rocprofv3 counter
-summary, if present), `kernels` (gate and blend GB/s at the 4K sizes, the 4K canvas step of
-20 tile attentions + blend in ms; with --full also the 2K canvas step and the gated 10-step
-run), `cpu_baseline` (the fp64 oracle on a bounded row sample, host cores).
+summary, if present; `device_state_during_launches` and `clock_limiter` say what held the shader
+clock while it ran), `kernels` (gate, blend, gain refresh and tile statistics GB/s at the 4K sizes,
+the tiny fp32, 2K and 4K canvas steps, the gated 10-step run and the 10-step refine run under the
+paper's own cache policy; --full adds the 48 x 64 head shape), `cpu_baseline` (the fp64 oracle on a
+bounded row sample, host cores).  Every input is drawn from a seeded generator.
 """
 import argparse
 import json
@@ -120,6 +122,126 @@ class DeviceStateSampler:
                 "shader_clock_mhz": mean(self.hz), "samples": max(len(self.w), len(self.hz)), "source": "sysfs (hwmon, pp_dpm_sclk)"}
 
 
+_LIMITER_CHILD = r"""
+import json, sys, time
+out = {}
+try:
+    import amdsmi
+    amdsmi.amdsmi_init()
+    h = amdsmi.amdsmi_get_processor_handles()[0]
+    def snap():
+        d = {}
+        try:
+            m = amdsmi.amdsmi_get_gpu_metrics_info(h)
+            for k, v in m.items():
+                if ("residency" in k or "throttle" in k or k in ("accumulation_counter", "current_gfxclk", "curr_socket_power",
+                                                                 "current_socket_power", "average_socket_power")):
+                    d[k] = v
+            xs = m.get("xcp_stats")
+            if isinstance(xs, list):
+                for k in ("gfx_below_host_limit_ppt_acc", "gfx_below_host_limit_thm_acc", "gfx_below_host_limit_total_acc",
+                          "gfx_low_utilization_acc", "gfx_below_host_limit_acc"):
+                    vals = [x.get(k) for x in xs if isinstance(x, dict) and k in x]
+                    if vals:
+                        d["xcp_" + k] = vals
+        except Exception as e:
+            d["metrics_error"] = str(e)[:120]
+        try:
+            d["violation"] = amdsmi.amdsmi_get_violation_status(h)
+        except Exception as e:
+            d["violation_error"] = str(e)[:120]
+        return d
+    out["a"] = snap()
+    time.sleep(float(sys.argv[1]))
+    out["b"] = snap()
+    amdsmi.amdsmi_shut_down()
+except Exception as e:
+    out["error"] = ("%s: %s" % (type(e).__name__, e))[:200]
+print(json.dumps(out, default=str))
+"""
+
+
+def clock_limiter(torch, enqueue, launches=40, window_s=1.5):
+    """Which limiter holds the shader clock under the attention kernel.  `launches` calls are enqueued (a few seconds
+    of GPU work) and, while they run, a child process reads the driver's metrics table twice, `window_s` apart, through
+    the amdsmi library (passive: it reads what the driver exposes in sysfs).  The firmware keeps one residency
+    accumulator per limiter (package power, socket / regulator / HBM temperature, PROCHOT) beside a common sample
+    counter: the share of the window each of them advanced is that limiter's activity.  Says so when the box does not
+    expose them."""
+    import subprocess
+    done = torch.cuda.Event()
+    for _ in range(launches):
+        enqueue()
+    done.record()
+    try:
+        r = subprocess.run([sys.executable, "-c", _LIMITER_CHILD, str(window_s)], capture_output=True, text=True, timeout=90)
+        still_running = not done.query()
+        torch.cuda.synchronize()
+        data = json.loads(r.stdout.strip().splitlines()[-1])
+    except Exception as e:                      # the report is an extra: never fail the bench over it
+        torch.cuda.synchronize()
+        return {"available": False, "why": ("%s: %s" % (type(e).__name__, e))[:160]}
+    if "error" in data or "a" not in data:
+        return {"available": False, "why": data.get("error", "no snapshot")}
+    a, b = data["a"], data["b"]
+
+    def num(v):
+        return v if isinstance(v, (int, float)) and not isinstance(v, bool) else None
+
+    rep = {"available": False, "read_while_launches_ran": bool(still_running), "window_s": window_s,
+           "source": "amdsmi library (gpu_metrics table in sysfs), two reads while the launches run"}
+    c0, c1 = num(a.get("accumulation_counter")), num(b.get("accumulation_counter"))
+    shares = {}
+    if c0 is not None and c1 is not None and c1 > c0:
+        for k in b:
+            if k.endswith("_residency_acc") and num(a.get(k)) is not None and num(b.get(k)) is not None:
+                shares[k[:-len("_residency_acc")]] = round(100.0 * (b[k] - a[k]) / (c1 - c0), 1)
+        for k in b:
+            if k.startswith("xcp_") and isinstance(b[k], list) and isinstance(a.get(k), list):
+                d = [y - x for x, y in zip(a[k], b[k]) if num(x) is not None and num(y) is not None]
+                if d:
+                    shares[k[4:-4] if k.endswith("_acc") else k[4:]] = round(100.0 * max(d) / (c1 - c0), 1)
+    va, vb = a.get("violation"), b.get("violation")
+    if isinstance(va, dict) and isinstance(vb, dict) and num(va.get("acc_counter")) is not None and num(vb.get("acc_counter")) is not None \
+            and vb["acc_counter"] > va["acc_counter"]:
+        for k, name in (("acc_gfx_clk_below_host_limit_pwr", "gfx_clk_below_host_limit_power"),
+                        ("acc_gfx_clk_below_host_limit_thm", "gfx_clk_below_host_limit_thermal")):
+            xa, xb = va.get(k), vb.get(k)
+            if isinstance(xa, list) and isinstance(xb, list) and xa and xb and isinstance(xa[0], list) and isinstance(xb[0], list):
+                d = [y - x for x, y in zip(xa[0], xb[0]) if num(x) is not None and num(y) is not None]
+                if d:     # per XCD; the largest share is reported
+                    shares[name] = round(100.0 * max(d) / (vb["acc_counter"] - va["acc_counter"]), 1)
+    if shares:
+        rep["available"] = True
+        rep["residency_pct_of_window"] = shares
+        rep["active_limiters"] = sorted(k for k, v in shares.items() if v > 0 and "low_utilization" not in k)
+    ts = b.get("throttle_status")
+    if ts not in (None, "N/A"):
+        rep["throttle_status"] = ts
+        rep["available"] = True
+    if b.get("indep_throttle_status") not in (None, "N/A"):
+        rep["indep_throttle_status"] = b.get("indep_throttle_status")
+        rep["available"] = True
+    vio = b.get("violation")
+    if isinstance(vio, dict):
+        act = {k[4:]: v for k, v in vio.items() if k.startswith("per_") and v not in ("N/A", None)}
+        flat = {}
+        for k, v in act.items():
+            if isinstance(v, list):
+                nums = [x for x in v if num(x) is not None]
+                if nums:
+                    flat[k] = max(nums)
+            elif num(v) is not None:
+                flat[k] = v
+        if flat:
+            rep["violation_activity_pct"] = flat
+            rep["available"] = True
+    if not rep["available"]:
+        rep["why"] = "the box exposes no throttle accounting (" + "; ".join(
+            str(x) for x in (b.get("metrics_error"), b.get("violation_error"), "throttle_status=%s" % ts) if x) + ")"
+    return rep
+
+
 def counter_summary(name):
     """key = value lines of a committed rocprofv3 counter summary under profiles/ (None if absent)."""
     path = os.path.join(ROOT, "profiles", name)
@@ -149,6 +271,21 @@ def achievable_peaks():
         return json.loads(r.stdout.strip().splitlines()[-1]) if r.returncode == 0 else None
     except Exception:
         return None
+
+
+def canvas_tile_inputs(torch, g):
+    """Packed [3][heads][T][th][tw][d] inputs of every tile, cut out of seeded canvas tensors Q, K, V (seeds g.seed,
+    g.seed + 7, g.seed + 14): the step-0 inputs of the gated workload."""
+    from synthetic import randn_tensor, torch_dtype
+    out = [torch.empty((3,) + g.tile_shape, dtype=torch_dtype(g.dtype), device="cuda") for _ in range(g.n_tiles)]
+    for j in range(3):                      # one canvas tensor alive at a time
+        canvas = randn_tensor(g.grid_shape, g.dtype, g.seed + 7 * j, device="cuda")
+        for i in range(g.n_tiles):
+            tr, tc = divmod(i, g.n_tile_cols)
+            r0, c0 = tr * g.stride_h, tc * g.stride_w
+            out[i][j].copy_(canvas[:, :, r0:r0 + g.tile_h, c0:c0 + g.tile_w, :])
+        del canvas
+    return out
 
 
 def build_tile_inputs(torch, g, n_tiles, seed):
@@ -222,11 +359,11 @@ def other_configs(torch, sg, args):
     res = {}
     g1 = CONFIGS["tiny_f32"]
     p1 = sg.make_problem(g1)
-    q1, k1, v1 = (torch.randn(g1.grid_shape, dtype=torch.float32, device="cuda") for _ in range(3))
+    q1, k1, v1 = (randn_tensor(g1.grid_shape, "f32", g1.seed + 7 * j, device="cuda") for j in range(3))
     tiles1 = [torch.empty(g1.tile_shape, dtype=torch.float32, device="cuda") for _ in range(g1.n_tiles)]
     canvas1 = torch.empty(g1.grid_shape, dtype=torch.float32, device="cuda")
     ms1 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p1, canvas1, tiles1, q=q1, k=k1, v=v1), 50, warmup=3)
-    res["step_tiny_f32"] = {"ms": round(ms1, 4), "tiles": g1.n_tiles, "note": "4 attention launches of 10 workgroups each + blend, back to back; graph replay takes as long, so kernel latency, not launch overhead",
+    res["step_tiny_f32"] = {"ms": round(ms1, 4), "tiles": g1.n_tiles, "note": "one attention launch over the 4 tiles (40 workgroups) + blend: two dependent launches on a nearly empty chip",
                             "TFLOP/s": round(g1.attention_flops_per_tile * g1.n_tiles / ms1 * 1e-9, 4)}
     # the same five launches captured once in a HIP graph and replayed (the step reads nothing back, so it captures as is)
     try:
@@ -248,7 +385,7 @@ def other_configs(torch, sg, args):
     if args.heads:
         g3 = replace(g3, heads=args.heads)
     p3 = sg.make_problem(g3)
-    q3, k3, v3 = (torch.randn(g3.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    q3, k3, v3 = (randn_tensor(g3.grid_shape, "bf16", g3.seed + 7 * j, device="cuda") for j in range(3))
     tiles3 = [torch.empty(g3.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g3.n_tiles)]
     canvas3 = torch.empty(g3.grid_shape, dtype=torch.bfloat16, device="cuda")
     ms3 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p3, canvas3, tiles3, q=q3, k=k3, v=v3), 2, warmup=1)
@@ -265,7 +402,8 @@ def other_configs(torch, sg, args):
         g5 = replace(g5, heads=args.heads)
     p5 = sg.make_problem(g5)
     n5 = g5.n_tiles
-    tile_x = [randn_tensor((3,) + g5.tile_shape, "bf16", g5.seed + i, device="cuda") for i in range(n5)]
+    # step 0: every tile's window of one seeded canvas (the 4K canvas of config 4's shape); later steps drift per tile
+    tile_x = canvas_tile_inputs(torch, g5)
     cache_x = [torch.zeros_like(t) for t in tile_x]
     cache_out = [torch.zeros(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
     has_cache = torch.zeros(n5, dtype=torch.uint8, device="cuda")
@@ -293,32 +431,37 @@ def other_configs(torch, sg, args):
                      canvas=canvas, eps=eps)
 
 
-def full_extras(torch, sg, args, kept):
-    """Inter-step cache policy figures at the 4K sizes: the refresh pass, ten steps through sg_refine_step, tile std."""
+def head64_extra(torch, sg):
+    """The 720p tile at the head shape of CogVideoX-1.5 (48 heads x 64, Section 8 "Workloads"): packed head_dim-64 path."""
     from dataclasses import replace
-    from synthetic import perturb_, randn_tensor, CONFIGS
-    res = {}
-    # the 720p tile at the head shape of CogVideoX-1.5 (48 heads x 64, Section 8 "Workloads"): packed head_dim-64 path
-    g64 = replace(CONFIGS["tile720p_bf16"], heads=48, head_dim=64)
+    from synthetic import randn_tensor, CONFIGS
+    g64 = replace(CONFIGS["tile720p_bf16"], heads=48, head_dim=64, seed=1064)
     p64 = sg.make_problem(g64)
-    x64 = [torch.randn(g64.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    x64 = [randn_tensor(g64.grid_shape, "bf16", g64.seed + 7 * j, device="cuda") for j in range(3)]
     o64 = torch.empty(g64.tile_shape, dtype=torch.bfloat16, device="cuda")
     ms64 = time_calls(torch, lambda: sg.sg_tile_attention(p64, x64[0], x64[1], x64[2], 0, 0, o64), 5)
     fl64 = 4.0 * g64.tile_tokens ** 2 * 64 * 48
-    res["attention_tile720p_48x64"] = {"ms": round(ms64, 3), "TFLOP/s": round(fl64 / ms64 * 1e-9, 1),
-                                       "frac_bf16_peak": round(fl64 / ms64 * 1e-9 / PEAK_BF16_TFLOPS, 4)}
-    del x64, o64
+    return {"attention_tile720p_48x64": {"ms": round(ms64, 3), "TFLOP/s": round(fl64 / ms64 * 1e-9, 1),
+                                         "frac_bf16_peak": round(fl64 / ms64 * 1e-9 / PEAK_BF16_TFLOPS, 4)}}
+
+
+def policy_extras(torch, sg, args, kept):
+    """The paper's own cache policy at the 4K sizes (Section 5.1 Equations 5-7; Section 5.2 Algorithm 2): the refresh
+    pass, ten steps through sg_refine_step, the tile statistics."""
+    from synthetic import perturb_, randn_tensor
+    res = {}
     g5, p5, n5, cache_out, scores, rec, ws, canvas, eps = (kept[k] for k in ("g5", "p5", "n5", "cache_out", "scores", "rec", "ws", "canvas", "eps"))
     tile_x = cache_x = None
     kept.pop("tile_x"); kept.pop("cache_x")
     del tile_x, cache_x
+    torch.cuda.empty_cache()
     # inter-step cache policy (gain, path length, residual reuse): the refresh pass alone, half the tiles
     # recomputed (reads O_t, O_{t-1}, I_t, writes delta: 10 B per element) and half reused (reads I_t, delta,
     # writes O_t: 8 B per element)
     E = int(np.prod(g5.tile_shape))
     o_cur = cache_out
-    o_prev = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
-    latent = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
+    o_prev = [randn_tensor(g5.tile_shape, "bf16", g5.seed + 300 + i, device="cuda") for i in range(n5)]
+    latent = [randn_tensor(g5.tile_shape, "bf16", g5.seed + 400 + i, device="cuda") for i in range(n5)]
     delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n5)]
     state = sg.GainState(n5)
     state.has_prev.fill_(1)
@@ -329,7 +472,7 @@ def full_extras(torch, sg, args, kept):
     # the same drift under the paper's policy (gain, path length, residual reuse) with region-aware thresholds
     # (MaxMin, adjusted every 2 steps) and the scheduler update fused behind the blend: sg_refine_step
     del o_prev, latent
-    xb = [[randn_tensor((3,) + g5.tile_shape, "bf16", g5.seed + i, device="cuda") for i in range(n5)], None]
+    xb = [canvas_tile_inputs(torch, g5), None]
     xb[1] = [torch.empty_like(t) for t in xb[0]]
     outs = [cache_out, [torch.zeros(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]]
     st2 = sg.GainState(n5)
@@ -355,9 +498,12 @@ def full_extras(torch, sg, args, kept):
         e1.record()
         e1.synchronize()
         per_step.append({"ms": round(e0.elapsed_time(e1), 2), "recomputed": int(rec.sum())})
-    res["refine_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1), "steps": per_step}
+    res["refine_4k_10_steps"] = {"total_ms": round(sum(x["ms"] for x in per_step), 1),
+                                 "recomputed": sum(x["recomputed"] for x in per_step), "of": n5 * g5.steps,
+                                 "what": "sg_refine_step: gain / path-length gate, attention, residual refresh, tile std + "
+                                         "MaxMin thresholds every 2 steps, Fuse + scheduler update", "steps": per_step}
     del xb, outs
-    o_cur = [torch.randn(g5.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n5)]
+    o_cur = [randn_tensor(g5.tile_shape, "bf16", g5.seed + 500 + i, device="cuda") for i in range(n5)]
     tstd = torch.empty(n5, dtype=torch.float32, device="cuda")
     ms_s = time_calls(torch, lambda: sg.sg_tile_std(o_cur, tstd, ws), 10)
     res["tile_std_4k"] = {"ms": round(ms_s, 4), "GB/s": round(2.0 * E * n5 / ms_s * 1e-6, 1),
@@ -375,7 +521,7 @@ def main():
     ap.add_argument("--workload", default="tile720p_bf16")
     ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
     ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
-    ap.add_argument("--full", action="store_true", help="also time the gain refresh, the 10-step refine run and the tile statistics at the 4K sizes")
+    ap.add_argument("--full", action="store_true", help="also time the 4K step with gathered tiles and the 720p tile at 48 heads x 64")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="query rows per head of the CPU baseline sample")
     ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the CPU baseline sample")
     args = ap.parse_args()
@@ -388,7 +534,7 @@ def main():
     import torch
     import paper_2508_17756_amd as sg
     from dataclasses import replace
-    from synthetic import CONFIGS, perturb_
+    from synthetic import CONFIGS, perturb_, randn_tensor
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -450,6 +596,7 @@ def main():
     ms_att = time_calls(torch, att, max(2, args.steps))
     with DeviceStateSampler() as sampler:
         ms_att_min, ms_att_median = time_each(torch, att, 10)
+    limiter = clock_limiter(torch, att)
     att_tflops = gt.attention_flops_per_tile / (ms_att * 1e-3) * 1e-12
     pmc = counter_summary("attention_bf16_tile720p_hbm_traffic.txt")
     traffic = None
@@ -468,7 +615,7 @@ def main():
                      "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                      "kernel": "attention_bf16_kernel", "ms_per_launch": round(ms_att, 3),
                      "ms_min_of_10": round(ms_att_min, 3), "ms_median_of_10": round(ms_att_median, 3),
-                     "device_state_during_launches": sampler.summary(),
+                     "device_state_during_launches": sampler.summary(), "clock_limiter": limiter,
                      "flops_per_launch": gt.attention_flops_per_tile},
     }
     if args.heads:
@@ -489,8 +636,8 @@ def main():
             g4 = replace(g4, heads=args.heads)
         p4 = sg.make_problem(g4)
         n4, E4 = g4.n_tiles, int(np.prod(g4.tile_shape))
-        cur4 = [torch.randn(3 * E4, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
-        old4 = [torch.randn(3 * E4, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
+        cur4 = [randn_tensor((3 * E4,), "bf16", g4.seed + 100 + i, device="cuda") for i in range(n4)]
+        old4 = [randn_tensor((3 * E4,), "bf16", g4.seed + 200 + i, device="cuda") for i in range(n4)]
         has4 = torch.ones(n4, dtype=torch.uint8, device="cuda")
         sc4 = torch.empty(n4, dtype=torch.float32, device="cuda")
         rc4 = torch.empty(n4, dtype=torch.uint8, device="cuda")
@@ -498,38 +645,42 @@ def main():
         ms_gate4 = time_calls(torch, lambda: sg.sg_cache_gate(cur4, old4, has4, 0.05, sc4, rc4, ws4), 10)
         kernels["gate_4k"] = dict(hbm(2.0 * 3 * E4 * 2 * n4, ms_gate4), tiles=n4)
         del cur4, old4
-        tiles4 = [torch.randn(g4.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n4)]
+        tiles4 = [randn_tensor(g4.tile_shape, "bf16", g4.seed + 300 + i, device="cuda") for i in range(n4)]
         canvas4 = torch.empty(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
         ms_blend = time_calls(torch, lambda: sg.sg_tile_blend(p4, tiles4, canvas4), 20)
         kernels["blend_4k"] = hbm(2.0 * (n4 * E4 + int(np.prod(g4.grid_shape))), ms_blend)
         # Fuse + scheduler update in one pass: also reads the latent canvas, writes the new latent in place
-        lat4 = torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda")
+        lat4 = randn_tensor(g4.grid_shape, "bf16", g4.seed + 400, device="cuda")
         ms_bu = time_calls(torch, lambda: sg.sg_tile_blend_update(p4, tiles4, lat4, 1.0, -0.02, lat4), 20)
         kernels["blend_update_4k"] = hbm(2.0 * (n4 * E4 + 2 * int(np.prod(g4.grid_shape))), ms_bu)
         del lat4
         # the 4K canvas step: 20 tile attentions read in place from the canvas tensors + blend
-        q4, k4, v4 = (torch.randn(g4.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        q4, k4, v4 = (randn_tensor(g4.grid_shape, "bf16", g4.seed + 7 * j, device="cuda") for j in range(3))
         ms4 = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4), 2, warmup=1)
-        kernels["step_4k_in_place"] = {"ms": round(ms4, 2), "tiles": n4,
-                                       "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4 * 1e-9, 1)}
-        # same step with a one-tile workspace: each tile's Q, K, V are gathered into packed form first
-        wsp = torch.empty(3 * E4 * 2, dtype=torch.uint8, device="cuda")
-        ms4g = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4, workspace=wsp),
-                          2, warmup=1)
-        kernels["step_4k"] = {"ms": round(ms4g, 2), "tiles": n4,
-                              "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4g * 1e-9, 1),
-                              "note": "tiles gathered into a packed workspace, then attended"}
-        del q4, k4, v4, tiles4, canvas4, wsp
+        kernels["step_4k"] = {"ms": round(ms4, 2), "tiles": n4,
+                              "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4 * 1e-9, 1),
+                              "note": "all 20 tiles read in place from the canvas tensors by one attention launch, then the blend"}
+        if args.full:
+            # same step with a one-tile workspace: each tile's Q, K, V are gathered into packed form first, tile by tile
+            wsp = torch.empty(3 * E4 * 2, dtype=torch.uint8, device="cuda")
+            ms4g = time_calls(torch, lambda: sg.sg_denoise_step_tiled(p4, canvas4, tiles4, q=q4, k=k4, v=v4, workspace=wsp),
+                              2, warmup=1)
+            kernels["step_4k_gathered"] = {"ms": round(ms4g, 2), "tiles": n4,
+                                           "TFLOP/s": round(g4.attention_flops_per_tile * n4 / ms4g * 1e-9, 1),
+                                           "note": "tiles gathered into a packed workspace, then attended one launch per tile"}
+            del wsp
+        del q4, k4, v4, tiles4, canvas4
         others, kept = other_configs(torch, sg, args)
         kernels.update(others)
-        if args.full:
-            kernels.update(full_extras(torch, sg, args, kept))
+        kernels.update(policy_extras(torch, sg, args, kept))
         del kept
+        if args.full:
+            kernels.update(head64_extra(torch, sg))
         out["kernels"] = kernels
         frac = lambda tf: round(tf / PEAK_BF16_TFLOPS, 4)
         out["configs"] = {
             "1_tiny_f32_step": {"ms": kernels["step_tiny_f32"]["ms"], "TFLOP/s": kernels["step_tiny_f32"]["TFLOP/s"],
-                                "bound": "kernel latency (10 workgroups per launch)"},
+                                "bound": "kernel latency (two dependent launches, 40 workgroups)"},
             "2_tile720p_bf16_step": {"ms": round(ms_step, 3), "TFLOP/s": round(value, 1), "frac_bf16_peak": frac(value)},
             "3_canvas2k_bf16_step": {"ms": kernels["step_2k"]["ms"], "TFLOP/s": kernels["step_2k"]["TFLOP/s"],
                                      "frac_bf16_peak": frac(kernels["step_2k"]["TFLOP/s"])},

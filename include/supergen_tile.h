@@ -104,8 +104,13 @@ int sg_workspace_bytes(int32_t n_tiles, size_t* out_bytes);
  *   q, k, v   device, canvas tensors (layout above); the tile is read in place, never copied
  *   out_tile  device, packed tile [heads][T][tile_h][tile_w][head_dim], 16-byte aligned
  * A packed tile is attended by describing it as a canvas that is one tile (H = tile_h,
- * W = tile_w, 1 x 1 tiles).  A shifted partition (shift_h or shift_w non-zero) is not read in
- * place (SG_ERR_UNSUPPORTED): gather the tile with sg_tile_slice and attend the packed copy.
+ * W = tile_w, 1 x 1 tiles).  Under a shifted partition (shift_h or shift_w non-zero) the tile's
+ * window is read at its shifted position, wrapping around the canvas edges where it crosses them
+ * (a window that wraps is read row by row and runs somewhat slower than one that does not; gathering
+ * it with sg_tile_slice and attending the packed copy is the faster route for large tiles).
+ * Q is multiplied by scale * log2(e) and rounded to bf16 once more before the products of a bf16
+ * problem (the score then leaves the matrix cores as the exponent): one extra bf16 rounding of the
+ * scores' left factor on top of "multiply in bf16, accumulate in fp32".
  */
 int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const void* v,
                       int32_t tile_row, int32_t tile_col, void* out_tile, void* stream);
@@ -205,16 +210,17 @@ typedef struct sg_step_io {
 /*
  * One stage-2 step over all tiles (Algorithm 1 loop body; Section 5.1: Tile Dispatcher ->
  * Threshold Comparator -> recompute or reuse -> Tile Fuser).
- *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  If
- *     `workspace` (256-byte aligned) holds at least one packed tile input, 3 * heads * T * tile_h *
- *     tile_w * head_dim elements, every tile is gathered into it (sg_tile_slice) and attended in
- *     packed form, which is faster than reading the canvas in place and is the only way under a
- *     shifted partition (SG_ERR_UNSUPPORTED without a workspace, SG_ERR_WORKSPACE with a small one).
+ *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  All
+ *     tiles are read in place and attended by one launch (two under a shifted partition: the windows
+ *     that wrap around a canvas edge and those that do not).  If `workspace` (256-byte aligned) holds
+ *     at least one packed tile input, 3 * heads * T * tile_h * tile_w * head_dim elements, every tile
+ *     is instead gathered into it (sg_tile_slice) and attended in packed form, tile by tile.
  *   cached mode: gate every tile on tile_x[i] against cache_x[i]; for the tiles to recompute
  *     cache_out[i] = attention(tile_x[i]), cache_x[i] = tile_x[i], has_cache[i] = 1; reused
  *     tiles keep their cache entries untouched (drift stays measured from the last recomputed
  *     step); grid_out = Fuse of all cache_out.
- * The decisions stay on the device: skipped tiles cost one empty launch, nothing is read back.
+ * The decisions stay on the device and nothing is read back: one attention launch covers all tiles
+ * and numbers only the work of the tiles to recompute.
  */
 int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* stream);
 

@@ -150,7 +150,9 @@ def gate_score(x_cur, x_cached):
 
 
 def cache_gate(x_cur, x_cached, has_cache, threshold):
-    """Per tile: recompute = (no cache) or (score >= threshold).
+    """Per tile: reuse only with a cache and a score strictly below the threshold
+    (Equation 7); everything else recomputes, which includes a tie and a NaN score
+    (NaN or Inf in the inputs: never "below").
 
     Returns (scores, recompute); the score of a tile without a cache is +inf.
     """
@@ -158,7 +160,7 @@ def cache_gate(x_cur, x_cached, has_cache, threshold):
     for xk, xc, hc in zip(x_cur, x_cached, has_cache):
         s = gate_score(xk, xc) if hc else float("inf")
         scores.append(s)
-        recompute.append(bool((not hc) or s >= float(threshold)))
+        recompute.append(not (bool(hc) and s < float(threshold)))
     return np.array(scores, dtype=np.float64), np.array(recompute, dtype=bool)
 
 

@@ -23,18 +23,11 @@
 // Built with -fno-honor-nans: a NaN in Q, K or V gives unspecified (not necessarily NaN) output.
 #include <type_traits>
 #include <atomic>
-#include "sg_common.h"
+#include "attention_common.h"
 
 namespace sg {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-#define SG_LDS __attribute__((address_space(3)))
 #define SG_INLINE __attribute__((always_inline))   // on the kernel's lambdas: a lambda left as a call pins every captured array in memory
 
 constexpr int kWaves = 8;
@@ -48,39 +41,16 @@ constexpr int kTileBytes = kBC * kRowBytes;          // one K (or V) stage: 16 K
 constexpr int kVRegion = kStages * kTileBytes;       // V stages start at 64 KiB
 constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // 128 KiB
 
-struct View16 {
-  uint32_t base16, st16, row_skip16, frame_skip16;
-  int32_t th, tw, N;
-  uint32_t head16;
-};
-struct RowCursor { int32_t i, j; uint32_t off16; };
-
-__device__ __forceinline__ RowCursor cursor_at(const View16& vw, int n) {
-  const int plane = vw.th * vw.tw;
-  const int t = n / plane, r = n - t * plane;
-  RowCursor c;
-  c.i = r / vw.tw;
-  c.j = r - c.i * vw.tw;
-  c.off16 = vw.base16 + (uint32_t)n * vw.st16 + (uint32_t)(t * vw.th + c.i) * vw.row_skip16 + (uint32_t)t * vw.frame_skip16;
-  return c;
-}
-__device__ __forceinline__ void cursor_advance(const View16& vw, RowCursor& c, int step) {
-  c.j += step;
-  c.off16 += (uint32_t)step * vw.st16;
-  while (c.j >= vw.tw) {
-    c.j -= vw.tw;
-    c.off16 += vw.row_skip16;
-    if (++c.i == vw.th) { c.i = 0; c.off16 += vw.frame_skip16; }
-  }
-}
-
 // 16 bytes per lane from global memory straight into LDS: lane i fills bytes [16 i, 16 i + 16) of the
 // 1 KiB block at LDS byte address `lds_dst` (wave-uniform).  Address = sbase + voff (32-bit byte offset).
 // Inline assembly keeps the compiler from ordering later LDS reads behind the transfer; completion is
-// awaited explicitly with wait_vmcnt.
+// awaited explicitly with wait_vmcnt.  The statement overwrites m0 and says so.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is a reserved register; naming it as clobbered is the point
 __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_dst) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_dst), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N == 0 || N == 4 || N == 8, "");
@@ -172,14 +142,12 @@ __device__ __forceinline__ float block_max(const f32x16 (&t)[kMaxSB]) {
 }
 constexpr float kOverflowGuard = 65536.0f;   // a stage's exponentials may grow to 2^16 before the reference moves
 
-enum { kPerLane = 0, kLinear = 1, kScalarWalk = 2 };   // how the loader walks the tile (see the DMA loader)
+enum { kPerLane = 0, kLinear = 1, kScalarWalk = 2, kWrapped = 3 };   // how the loader walks the tile (see the DMA loader)
 
 template <int D, int MODE>
 __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 vw, const float c_log2, const int heads,
-                                                                  const int n_qblocks, const int per_xcd,
-                                                                  const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
-                                                                  const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
-                                                                  const uint8_t* __restrict__ run_flag) {
+                                                                  const int n_qblocks, const int n_tiles, const AttnTable tab,
+                                                                  const uint8_t* __restrict__ run_flags) {
   static_assert(D == 128 || D == 64, "head_dim 64 or 128");
   static_assert(D == 128 || MODE == kLinear, "head_dim 64 streams packed tiles only");
   // LDS rows ("slots") are always 256 bytes.  With head_dim 128 a slot is one key and a stage 64 keys; with
@@ -188,17 +156,34 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // the pairing of fragments with accumulators differs (see qk and pv).
   constexpr int kSB = (D == 128) ? 2 : 4;   // 32-key score blocks per stage
   constexpr int kKeys = 32 * kSB;           // keys per stage
-  if (run_flag && !*run_flag) return;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD walks a contiguous range
-  // of (head, query block) pairs and its CUs stream the same head's K/V through one L2.
+  // Work = (active tile, head, query block) triples, query block fastest.  Workgroups are dealt round-robin
+  // to the 8 XCDs; renumber so that each XCD walks a contiguous range of the work and its CUs stream the same
+  // head's K/V through one L2.  Only the tiles whose run flag is set are numbered, so the work is spread
+  // evenly over the XCDs whichever tiles the gate reuses; the rest of the grid exits here.
+  const uint32_t active = attn_active_mask(run_flags, n_tiles);
+  const int per_tile = heads * n_qblocks;
+  const int total = __builtin_popcount(active) * per_tile;
+  const int per_xcd = (total + kXcd - 1) / kXcd;
   const int xcd = blockIdx.x % kXcd, slot = blockIdx.x / kXcd;
   const int logical = xcd * per_xcd + slot;
-  if (logical >= heads * n_qblocks) return;
-  const int head = logical / n_qblocks, qblk = logical - head * n_qblocks;
+  if (slot >= per_xcd || logical >= total) return;
+  const int nth = logical / per_tile, in_tile = logical - nth * per_tile;
+  const int tile = __builtin_amdgcn_readfirstlane(attn_nth_tile(active, nth));
+  const int head = in_tile / n_qblocks, qblk = in_tile - head * n_qblocks;
+  const u32x4* const qg = (const u32x4*)tab.q[tile];
+  const u32x4* const kg = (const u32x4*)tab.k[tile];
+  const u32x4* const vg = (const u32x4*)tab.v[tile];
+  uint16_t* const out = (uint16_t*)tab.out[tile];
+  const int wy0 = (MODE == kWrapped) ? tab.y0[tile] : 0, wx0 = (MODE == kWrapped) ? tab.x0[tile] : 0;
+  // offset of tile token n from the tile's pointers, in 16-byte units
+  auto token_off16 = [&](int n) SG_INLINE -> uint32_t {
+    if (MODE == kWrapped) return wrap_offset16(vw, wrap_cursor_at(vw, n), wy0, wx0);
+    return cursor_at(vw, n).off16;
+  };
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -214,8 +199,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   {
     int n = q0 + lq;
     if (n > N - 1) n = N - 1;
-    const RowCursor cq = cursor_at(vw, n);
-    const u32x4* src = qg + head_off16 + cq.off16;
+    const u32x4* src = qg + head_off16 + token_off16(n);
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) {
       const u32x4 raw = src[2 * kk + half];
@@ -251,6 +235,9 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   // a wave-uniform 64-bit pointer that walks the tile (scalar registers, scalar ALU) and a per-lane byte
   // offset that never changes, so the steady loop spends no vector instructions on addressing.
   // kPerLane: every lane walks its own row with a cursor and 32-bit offsets from the head's base.
+  // kWrapped: the same for the wrapped window of a shifted partition; the offset is formed from the token's
+  // coordinates each time, since a tile row may cross the canvas edge.
+  constexpr bool kLaneWalk = (MODE == kPerLane || MODE == kWrapped);
   const int ld_sub = lane >> 4, ld_slot = lane & 15;
   uint32_t kchunk[2], vchunk[2];
 #pragma unroll
@@ -259,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     kchunk[u] = ld_slot ^ (row & 15);
     vchunk[u] = ld_slot ^ ((row & 3) << 2);
   }
-  const uint32_t last16 = cursor_at(vw, N - 1).off16;   // the last valid row: stands in for rows >= N
+  const uint32_t last16 = token_off16(N - 1);   // the last valid row: stands in for rows >= N
   const uint32_t dma_dst = lds0 + wave * (8 * kRowBytes);
   // scalar walk: pointers to row 8w of the stage to issue (K and V), its tile row / column, lane offsets
   const char* kcur = (const char*)kh;
@@ -268,6 +255,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   uint32_t klane[2], vlane[2];
   // per-lane walk
   RowCursor cur[2];
+  WrapCursor wcur[2];
   uint32_t koff[2], voff[2];              // byte offsets from kh / vh of the next stage to issue
   // head_dim 64: key (within a stage) whose chunk this lane moves, for K and for V
   int ktok[2], vtok[2];
@@ -277,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
     ktok[u] = 64 * (slot_u >> 5) + 32 * (int)(kchunk[u] >> 3) + (slot_u & 31);
     vtok[u] = 64 * (slot_u >> 5) + 32 * (int)(vchunk[u] >> 3) + (slot_u & 31);
   }
-  if (MODE != kPerLane) {
+  if (!kLaneWalk) {
     const int n0 = (D == 128) ? 8 * wave : 0;
     const RowCursor c = cursor_at(vw, n0 < N ? n0 : 0);
     row_i = __builtin_amdgcn_readfirstlane(c.i);
@@ -299,11 +287,31 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int row = 8 * wave + 4 * u + ld_sub;
-      cur[u] = cursor_at(vw, row < N ? row : N - 1);
-      koff[u] = (cur[u].off16 + kchunk[u]) << 4;
-      voff[u] = (cur[u].off16 + vchunk[u]) << 4;
+      uint32_t off16;
+      if (MODE == kWrapped) {
+        wcur[u] = wrap_cursor_at(vw, row < N ? row : N - 1);
+        off16 = wrap_offset16(vw, wcur[u], wy0, wx0);
+      } else {
+        cur[u] = cursor_at(vw, row < N ? row : N - 1);
+        off16 = cur[u].off16;
+      }
+      koff[u] = (off16 + kchunk[u]) << 4;
+      voff[u] = (off16 + vchunk[u]) << 4;
     }
   }
+  // per-lane walk: row u of this lane moves one stage on (only while the new row exists)
+  auto lane_advance = [&](int u, int n) SG_INLINE {
+    uint32_t off16;
+    if (MODE == kWrapped) {
+      if (n + kKeys < N) wrap_cursor_advance(vw, wcur[u], kKeys);
+      off16 = wrap_offset16(vw, wcur[u], wy0, wx0);
+    } else {
+      if (n + kKeys < N) cursor_advance(vw, cur[u], kKeys);
+      off16 = cur[u].off16;
+    }
+    koff[u] = (off16 + kchunk[u]) << 4;
+    voff[u] = (off16 + vchunk[u]) << 4;
+  };
   const uint64_t stage_bytes = (uint64_t)(kKeys * 16) * vw.st16;
   const uint64_t row_skip_bytes = (uint64_t)vw.row_skip16 << 4, frame_skip_bytes = (uint64_t)vw.frame_skip16 << 4;
   auto scalar_advance = [&]() SG_INLINE {   // the wavefront's rows move one stage on
@@ -332,19 +340,16 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   auto issue_full = [&](int blk, int st) SG_INLINE {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      if (MODE != kPerLane) {
+      if (!kLaneWalk) {
         dma16(kcur, klane[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vcur, vlane[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
       } else {
         dma16(kh, koff[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vh, voff[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-        const int n = blk * kKeys + 8 * wave + 4 * u + ld_sub;
-        if (n + kKeys < N) cursor_advance(vw, cur[u], kKeys);
-        koff[u] = (cur[u].off16 + kchunk[u]) << 4;
-        voff[u] = (cur[u].off16 + vchunk[u]) << 4;
+        lane_advance(u, blk * kKeys + 8 * wave + 4 * u + ld_sub);
       }
     }
-    if (MODE != kPerLane) scalar_advance();
+    if (!kLaneWalk) scalar_advance();
   };
   // same for a stage that may hold rows >= N: those lanes fetch the last valid row (masked later)
   auto issue_any = [&](int blk, int st) SG_INLINE {
@@ -358,7 +363,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
         const uint32_t vo = (n0 + vtok[u] < N) ? vlane[u] : back + ((vchunk[u] & 7) << 4);
         dma16(kcur, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vcur, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-      } else if (MODE != kPerLane) {
+      } else if (!kLaneWalk) {
         if (n0 + 7 < N) {          // all 8 rows valid
           dma16(kcur, klane[u], dma_dst + st * kTileBytes + u * (4 * kRowBytes));
           dma16(vcur, vlane[u], dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
@@ -378,12 +383,10 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
         const uint32_t vo = (n < N) ? voff[u] : ((last16 + vchunk[u]) << 4);
         dma16(kh, ko, dma_dst + st * kTileBytes + u * (4 * kRowBytes));
         dma16(vh, vo, dma_dst + kVRegion + st * kTileBytes + u * (4 * kRowBytes));
-        if (n + kKeys < N) cursor_advance(vw, cur[u], kKeys);
-        koff[u] = (cur[u].off16 + kchunk[u]) << 4;
-        voff[u] = (cur[u].off16 + vchunk[u]) << 4;
+        lane_advance(u, n);
       }
     }
-    if (MODE != kPerLane && n0 + kKeys < N) scalar_advance();
+    if (!kLaneWalk && n0 + kKeys < N) scalar_advance();
   };
 
   f32x16 oacc[D / 32];
@@ -642,55 +645,62 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
 
 }  // namespace
 
-int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
-                          const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
+int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b, hipStream_t s) {
   if (head_dim != 128 && head_dim != 64) return SG_ERR_UNSUPPORTED;
+  if (b.n_tiles <= 0) return SG_OK;
+  const bool linear = (tv.W == tv.tw && tv.H == tv.th) && !tv.wrapped;
   // head_dim 64 streams packed tiles only (two keys share an LDS slot, 32 keys apart: not one tile row);
   // tiles read in place from a canvas take the register-staged kernel
-  if (head_dim == 64 && !(tv.W == tv.tw && tv.H == tv.th))
-    return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
-  View16 vw;
-  vw.base16 = (uint32_t)(tv.base / 8);
-  vw.st16 = (uint32_t)(tv.stride_token / 8);
-  vw.row_skip16 = (uint32_t)(tv.W - tv.tw) * vw.st16;
-  vw.frame_skip16 = (uint32_t)((int64_t)(tv.H - tv.th) * tv.W) * vw.st16;
-  vw.th = tv.th; vw.tw = tv.tw; vw.N = tv.N;
-  vw.head16 = (uint32_t)(tv.stride_head / 8);
+  if (head_dim == 64 && !linear) return launch_attention_bf16_generic(tv, heads, head_dim, scale, b, s);
+  const View16 vw = make_view16(tv);
   // a wavefront moves 8 consecutive tile tokens per stage: contiguous in memory whenever they cannot
   // straddle a tile row (tile width a multiple of 8) or the tile rows are themselves adjacent (packed tile)
-  const bool linear = (tv.W == tv.tw && tv.H == tv.th);
-  const int mode = linear ? kLinear : (tv.tw % 8 == 0 ? kScalarWalk : kPerLane);
+  const int mode = tv.wrapped ? kWrapped : (linear ? kLinear : (tv.tw % 8 == 0 ? kScalarWalk : kPerLane));
   // The per-lane cursors address a head's K/V with 32-bit byte offsets from a wave-uniform base; canvases
   // whose per-head extent does not fit take the kernel with 64-bit addressing.
-  const int64_t head_extent = ((int64_t)tv.T * tv.H * tv.W) * tv.stride_token + tv.base;
-  if (mode == kPerLane && head_extent * 2 >= (1ll << 32))
-    return launch_attention_bf16_generic(tv, heads, head_dim, scale, q, k, v, out, run_flag, s);
+  const int64_t head_extent = ((int64_t)tv.T * tv.H * tv.W) * tv.stride_token;
+  if ((mode == kPerLane || mode == kWrapped) && head_extent * 2 >= (1ll << 32))
+    return launch_attention_bf16_generic(tv, heads, head_dim, scale, b, s);
   const int n_qblocks = (tv.N + kBR - 1) / kBR;
-  const int total = n_qblocks * heads;
-  const int per_xcd = (total + kXcd - 1) / kXcd;
   const float c_log2 = scale * 1.4426950408889634f;
-  dim3 grid(per_xcd * kXcd);
   // the kernels need more dynamic LDS than the default limit; the attribute is set once per device and kernel
   constexpr int kMaxDevices = 64;
-  static std::atomic<bool> attr_set[kMaxDevices][4];   // zero-initialised; set twice by racing threads is harmless
+  static std::atomic<bool> attr_set[kMaxDevices][5];   // zero-initialised; set twice by racing threads is harmless
   int dev = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
-  auto launch = [&](auto kern, int slot) -> int {
-    if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
-      SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-      if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
+  for (int t0 = 0; t0 < b.n_tiles; t0 += kAttnTilesPerLaunch) {
+    const int n = (b.n_tiles - t0 < kAttnTilesPerLaunch) ? b.n_tiles - t0 : kAttnTilesPerLaunch;
+    AttnTable tab;
+    for (int i = 0; i < kAttnTilesPerLaunch; ++i) {
+      const bool in = i < n;
+      tab.q[i] = in ? b.q[t0 + i] : nullptr;
+      tab.k[i] = in ? b.k[t0 + i] : nullptr;
+      tab.v[i] = in ? b.v[t0 + i] : nullptr;
+      tab.out[i] = in ? b.out[t0 + i] : nullptr;
+      tab.y0[i] = (in && b.y0) ? b.y0[t0 + i] : 0;
+      tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
     }
-    kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                           (const u32x4*)v, (uint16_t*)out, run_flag);
-    return SG_OK;
-  };
-  int st = SG_OK;
-  if (head_dim == 64) st = launch(attention_bf16_kernel<64, kLinear>, 3);
-  else if (mode == kLinear) st = launch(attention_bf16_kernel<128, kLinear>, kLinear);
-  else if (mode == kScalarWalk) st = launch(attention_bf16_kernel<128, kScalarWalk>, kScalarWalk);
-  else st = launch(attention_bf16_kernel<128, kPerLane>, kPerLane);
-  if (st != SG_OK) return st;
-  SG_HIP_TRY(hipGetLastError());
+    const int64_t total = (int64_t)n * heads * n_qblocks;   // the grid covers every tile; skipped tiles' share exits at once
+    if (total > (1ll << 31) - 2 * kXcd) return SG_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(((total + kXcd - 1) / kXcd) * kXcd));
+    const uint8_t* flags = b.run_flags ? b.run_flags + t0 : nullptr;
+    auto launch = [&](auto kern, int slot) -> int {
+      if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
+        SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
+      }
+      kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, n, tab, flags);
+      return SG_OK;
+    };
+    int st = SG_OK;
+    if (head_dim == 64) st = launch(attention_bf16_kernel<64, kLinear>, 4);
+    else if (mode == kLinear) st = launch(attention_bf16_kernel<128, kLinear>, kLinear);
+    else if (mode == kScalarWalk) st = launch(attention_bf16_kernel<128, kScalarWalk>, kScalarWalk);
+    else if (mode == kWrapped) st = launch(attention_bf16_kernel<128, kWrapped>, kWrapped);
+    else st = launch(attention_bf16_kernel<128, kPerLane>, kPerLane);
+    if (st != SG_OK) return st;
+    SG_HIP_TRY(hipGetLastError());
+  }
   return SG_OK;
 }
 

@@ -15,18 +15,12 @@
 // B-operand layout of  O^T = V^T P^T.  V^T fragments come out of LDS through the transposing
 // read (ds_read_b64_tr_b16); K and V rows are stored with XOR-swizzled 16-byte chunks so that
 // both fragment reads are bank-conflict free.
-#include "sg_common.h"
+#include <atomic>
+#include "attention_common.h"
 
 namespace sg {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-#define SG_LDS __attribute__((address_space(3)))
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
@@ -34,42 +28,6 @@ constexpr int kQB = 1;                    // 32-query sub-blocks per wavefront
 constexpr int kBR = kWaves * kQB * 32;    // 256 query rows per workgroup
 constexpr int kBC = 64;                   // keys per LDS stage
 constexpr int kXcd = 8;
-
-// Device-side copy of the tile addressing with 16-byte units (8 bf16) so offsets fit 32 bits.
-struct View16 {
-  uint32_t base16;     // tile origin
-  uint32_t st16;       // 16-byte units per canvas token
-  uint32_t row_skip16; // (W - tw) * st16: jump at the end of a tile row
-  uint32_t frame_skip16; // (H - th) * W * st16: jump at the end of a tile frame
-  int32_t th, tw, N;
-  uint32_t head16;     // 16-byte units per head (canvas tensors)
-};
-
-struct RowCursor {  // walks tile tokens n, n+kBC, n+2*kBC, ...
-  int32_t i, j;
-  uint32_t off16;
-};
-
-__device__ __forceinline__ RowCursor cursor_at(const View16& vw, int n) {
-  const int plane = vw.th * vw.tw;
-  const int t = n / plane, r = n - t * plane;
-  RowCursor c;
-  c.i = r / vw.tw;
-  c.j = r - c.i * vw.tw;
-  // canvas token index = (t*H + i)*W + j = n + (t*th + i)*(W - tw) + t*(H - th)*W
-  c.off16 = vw.base16 + (uint32_t)n * vw.st16 + (uint32_t)(t * vw.th + c.i) * vw.row_skip16 + (uint32_t)t * vw.frame_skip16;
-  return c;
-}
-
-__device__ __forceinline__ void cursor_advance(const View16& vw, RowCursor& c, int step) {
-  c.j += step;
-  c.off16 += (uint32_t)step * vw.st16;
-  while (c.j >= vw.tw) {
-    c.j -= vw.tw;
-    c.off16 += vw.row_skip16;
-    if (++c.i == vw.th) { c.i = 0; c.off16 += vw.frame_skip16; }
-  }
-}
 
 // LDS stage: K[64][128] then V[64][128] bf16, rows of 256 bytes = 16 chunks of 16 bytes.
 // K chunk c of row r is stored at chunk c ^ (r & 15); V chunk c of row r at c ^ ((r & 3) << 2).
@@ -135,23 +93,39 @@ __device__ __forceinline__ float softmax_block(f32x16 (&s)[2], Softmax& st, cons
   return alpha;
 }
 
-template <int D, bool LINEAR>
+enum { kCursor = 0, kLinearRows = 1, kWrappedRows = 2 };   // how the loader finds a tile token
+
+template <int D, int MODE>
 __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const View16 vw, const float c_log2, const int heads,
-                                                                  const int n_qblocks, const int per_xcd,
-                                                                  const u32x4* __restrict__ qg, const u32x4* __restrict__ kg,
-                                                                  const u32x4* __restrict__ vg, uint16_t* __restrict__ out,
-                                                                  const uint8_t* __restrict__ run_flag) {
+                                                                  const int n_qblocks, const int n_tiles, const AttnTable tab,
+                                                                  const uint8_t* __restrict__ run_flags) {
   static_assert((D == 128 || D == 64) && kQB == 1 && kBC == 64, "head_dim 64 or 128, one 32-query block per wavefront, 64-key stages");
-  if (run_flag && !*run_flag) return;
+  constexpr bool LINEAR = MODE == kLinearRows;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   SG_LDS uint8_t* const lds = (SG_LDS uint8_t*)smem;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; renumber so that each XCD walks a contiguous
-  // range of (head, query block) pairs and its 32 CUs stream the same head's K/V through one L2.
+  // Work = (active tile, head, query block), query block fastest; workgroups are dealt round-robin to the
+  // 8 XCDs and renumbered so that each XCD walks a contiguous range and streams the same head's K/V through
+  // its own L2.  Tiles whose run flag is 0 are not numbered; the rest of the grid exits here.
+  const uint32_t active = attn_active_mask(run_flags, n_tiles);
+  const int per_tile = heads * n_qblocks;
+  const int total = __builtin_popcount(active) * per_tile;
+  const int per_xcd = (total + kXcd - 1) / kXcd;
   const int xcd = blockIdx.x % kXcd, slot = blockIdx.x / kXcd;
   const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= heads * n_qblocks) return;
-  const int head = logical / n_qblocks, qblk = logical - head * n_qblocks;
+  if (slot >= per_xcd || logical >= total) return;
+  const int nth = logical / per_tile, in_tile = logical - nth * per_tile;
+  const int tile = __builtin_amdgcn_readfirstlane(attn_nth_tile(active, nth));
+  const int head = in_tile / n_qblocks, qblk = in_tile - head * n_qblocks;
+  const u32x4* const qg = (const u32x4*)tab.q[tile];
+  const u32x4* const kg = (const u32x4*)tab.k[tile];
+  const u32x4* const vg = (const u32x4*)tab.v[tile];
+  uint16_t* const out = (uint16_t*)tab.out[tile];
+  const int wy0 = (MODE == kWrappedRows) ? tab.y0[tile] : 0, wx0 = (MODE == kWrappedRows) ? tab.x0[tile] : 0;
+  auto token_off16 = [&](int n) __attribute__((always_inline)) -> uint32_t {
+    if (MODE == kWrappedRows) return wrap_offset16(vw, wrap_cursor_at(vw, n), wy0, wx0);
+    return cursor_at(vw, n).off16;
+  };
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 31, half = lane >> 5;
@@ -167,8 +141,7 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
   for (int qb = 0; qb < kQB; ++qb) {
     int n = q0 + 32 * qb + lq;
     if (n > N - 1) n = N - 1;
-    const RowCursor cq = cursor_at(vw, n);
-    const u32x4* src = qg + head_off16 + cq.off16;
+    const u32x4* src = qg + head_off16 + token_off16(n);
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, src[2 * kk + half]);
   }
@@ -180,15 +153,14 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
   constexpr int kLdRows = kThreads / kChunks, kLdSlots = kBC / kLdRows;
   static_assert(kLdSlots >= 1 && kLdRows * kLdSlots == kBC, "the workgroup's threads tile a stage exactly");
   RowCursor cur[kLdSlots];
-  uint32_t last16;
-  {
-    const RowCursor cl = cursor_at(vw, N - 1);
-    last16 = cl.off16;
+  WrapCursor wcur[kLdSlots];
+  const uint32_t last16 = token_off16(N - 1);
 #pragma unroll
-    for (int u = 0; u < kLdSlots; ++u) {
-      if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = vw.base16 + (uint32_t)(ld_row + kLdRows * u) * vw.st16; }
-      else cur[u] = cursor_at(vw, (ld_row + kLdRows * u < N) ? ld_row + kLdRows * u : N - 1);
-    }
+  for (int u = 0; u < kLdSlots; ++u) {
+    const int row = ld_row + kLdRows * u;
+    if (LINEAR) { cur[u].i = 0; cur[u].j = 0; cur[u].off16 = (uint32_t)row * vw.st16; }
+    else if (MODE == kWrappedRows) { wcur[u] = wrap_cursor_at(vw, row < N ? row : N - 1); cur[u].off16 = wrap_offset16(vw, wcur[u], wy0, wx0); }
+    else cur[u] = cursor_at(vw, row < N ? row : N - 1);
   }
   u32x4 kreg[kLdSlots], vreg[kLdSlots];
   auto load_stage = [&](int blk) {
@@ -199,7 +171,10 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
       kreg[u] = kh[off];
       vreg[u] = vh[off];
       if (LINEAR) cur[u].off16 += kBC * vw.st16;
-      else if (n + kBC < N) cursor_advance(vw, cur[u], kBC);
+      else if (n + kBC < N) {
+        if (MODE == kWrappedRows) { wrap_cursor_advance(vw, wcur[u], kBC); cur[u].off16 = wrap_offset16(vw, wcur[u], wy0, wx0); }
+        else cursor_advance(vw, cur[u], kBC);
+      }
     }
   };
   auto store_stage = [&](int buf) {
@@ -311,34 +286,56 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_generic_kernel(const 
 
 }  // namespace
 
-int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const void* q, const void* k,
-                          const void* v, void* out, const uint8_t* run_flag, hipStream_t s) {
+int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b, hipStream_t s) {
   if (head_dim != 128 && head_dim != 64) return SG_ERR_UNSUPPORTED;
-  View16 vw;
-  vw.base16 = (uint32_t)(tv.base / 8);
-  vw.st16 = (uint32_t)(tv.stride_token / 8);
-  vw.row_skip16 = (uint32_t)(tv.W - tv.tw) * vw.st16;
-  vw.frame_skip16 = (uint32_t)((int64_t)(tv.H - tv.th) * tv.W) * vw.st16;
-  vw.th = tv.th; vw.tw = tv.tw; vw.N = tv.N;
-  vw.head16 = (uint32_t)(tv.stride_head / 8);
-  const bool linear = (tv.W == tv.tw && tv.H == tv.th);
+  if (b.n_tiles <= 0) return SG_OK;
+  const View16 vw = make_view16(tv);
+  const int mode = tv.wrapped ? kWrappedRows : ((tv.W == tv.tw && tv.H == tv.th) ? kLinearRows : kCursor);
   const int n_qblocks = (tv.N + kBR - 1) / kBR;
-  const int total = n_qblocks * heads;
-  const int per_xcd = (total + kXcd - 1) / kXcd;
   const float c_log2 = scale * 1.4426950408889634f;
   const size_t lds = 2 * kStageBytes;
-  dim3 grid(per_xcd * kXcd);
-  auto launch = [&](auto kern) -> int {
-    SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, per_xcd, (const u32x4*)q, (const u32x4*)k,
-                                     (const u32x4*)v, (uint16_t*)out, run_flag);
-    return SG_OK;
-  };
-  int st;
-  if (head_dim == 128) st = linear ? launch(attention_bf16_generic_kernel<128, true>) : launch(attention_bf16_generic_kernel<128, false>);
-  else st = linear ? launch(attention_bf16_generic_kernel<64, true>) : launch(attention_bf16_generic_kernel<64, false>);
-  if (st != SG_OK) return st;
-  SG_HIP_TRY(hipGetLastError());
+  // the dynamic-LDS size is declared once per device and kernel (not per launch, so not inside a later capture)
+  constexpr int kMaxDevices = 64;
+  static std::atomic<bool> attr_set[kMaxDevices][6];   // zero-initialised; set twice by racing threads is harmless
+  int dev = 0;
+  SG_HIP_TRY(hipGetDevice(&dev));
+  for (int t0 = 0; t0 < b.n_tiles; t0 += kAttnTilesPerLaunch) {
+    const int n = (b.n_tiles - t0 < kAttnTilesPerLaunch) ? b.n_tiles - t0 : kAttnTilesPerLaunch;
+    AttnTable tab;
+    for (int i = 0; i < kAttnTilesPerLaunch; ++i) {
+      const bool in = i < n;
+      tab.q[i] = in ? b.q[t0 + i] : nullptr;
+      tab.k[i] = in ? b.k[t0 + i] : nullptr;
+      tab.v[i] = in ? b.v[t0 + i] : nullptr;
+      tab.out[i] = in ? b.out[t0 + i] : nullptr;
+      tab.y0[i] = (in && b.y0) ? b.y0[t0 + i] : 0;
+      tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
+    }
+    const int64_t total = (int64_t)n * heads * n_qblocks;
+    if (total > (1ll << 31) - 2 * kXcd) return SG_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(((total + kXcd - 1) / kXcd) * kXcd));
+    const uint8_t* flags = b.run_flags ? b.run_flags + t0 : nullptr;
+    auto launch = [&](auto kern, int slot) -> int {
+      if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
+        SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
+      }
+      kern<<<grid, kThreads, lds, s>>>(vw, c_log2, heads, n_qblocks, n, tab, flags);
+      return SG_OK;
+    };
+    int st;
+    if (head_dim == 128) {
+      if (mode == kLinearRows) st = launch(attention_bf16_generic_kernel<128, kLinearRows>, 0);
+      else if (mode == kWrappedRows) st = launch(attention_bf16_generic_kernel<128, kWrappedRows>, 1);
+      else st = launch(attention_bf16_generic_kernel<128, kCursor>, 2);
+    } else {
+      if (mode == kLinearRows) st = launch(attention_bf16_generic_kernel<64, kLinearRows>, 3);
+      else if (mode == kWrappedRows) st = launch(attention_bf16_generic_kernel<64, kWrappedRows>, 4);
+      else st = launch(attention_bf16_generic_kernel<64, kCursor>, 5);
+    }
+    if (st != SG_OK) return st;
+    SG_HIP_TRY(hipGetLastError());
+  }
   return SG_OK;
 }
 

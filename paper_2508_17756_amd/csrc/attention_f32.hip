@@ -6,7 +6,7 @@
 // (running max / running sum) form, which is algebraically the two-pass softmax.  The four
 // partial states (m, l, o) of a query are merged through LDS at the end.
 #include <atomic>
-#include "sg_common.h"
+#include "attention_common.h"
 
 namespace sg {
 namespace {
@@ -15,19 +15,31 @@ constexpr int kQ = 64;       // queries per workgroup
 constexpr int kSplit = 4;    // wavefronts per workgroup, each on its own share of the keys
 constexpr int kKC = 32;      // keys per wavefront and LDS chunk
 
-__device__ __forceinline__ int64_t token_offset(const TileView& tv, int n) {
+// element offset of tile token n from the tile's pointers (head 0); a wrapped window (shifted partition)
+// starts at canvas position (y0, x0) and wraps around both canvas edges
+__device__ __forceinline__ int64_t token_offset(const TileView& tv, int n, int y0, int x0) {
   const int plane = tv.th * tv.tw;
   const int t = n / plane, r = n - t * plane;
-  const int i = r / tv.tw, j = r - i * tv.tw;
-  return tv.base + (((int64_t)t * tv.H + i) * tv.W + j) * tv.stride_token;
+  int i = r / tv.tw, j = r - i * tv.tw;
+  if (tv.wrapped) {
+    i += y0; j += x0;
+    i -= (i >= tv.H) ? tv.H : 0;
+    j -= (j >= tv.W) ? tv.W : 0;
+  }
+  return (((int64_t)t * tv.H + i) * tv.W + j) * tv.stride_token;
 }
 
+// grid: (query blocks, heads, tiles of the launch); a tile whose run flag is 0 is skipped
 template <int D>
-__global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileView tv, const float scale,
-                                                                    const float* __restrict__ q, const float* __restrict__ k,
-                                                                    const float* __restrict__ v, float* __restrict__ out,
-                                                                    const uint8_t* __restrict__ run_flag) {
-  if (run_flag && !*run_flag) return;
+__global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileView tv, const float scale, const AttnTable tab,
+                                                                    const uint8_t* __restrict__ run_flags) {
+  const int tile = blockIdx.z;
+  if (run_flags && !run_flags[tile]) return;
+  const float* __restrict__ q = (const float*)tab.q[tile];
+  const float* __restrict__ k = (const float*)tab.k[tile];
+  const float* __restrict__ v = (const float*)tab.v[tile];
+  float* __restrict__ out = (float*)tab.out[tile];
+  const int y0 = tab.y0[tile], x0 = tab.x0[tile];
   // [wavefront][key][d] chunks of K and V; after the key loop the same memory holds the partial outputs
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float (*sK)[kKC][D] = (float (*)[kKC][D])smem;
@@ -40,7 +52,7 @@ __global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileVi
 
   float qr[D], o[D];
   {
-    const float4* src = (const float4*)(q + hoff + token_offset(tv, valid ? n : tv.N - 1));
+    const float4* src = (const float4*)(q + hoff + token_offset(tv, valid ? n : tv.N - 1, y0, x0));
 #pragma unroll
     for (int c = 0; c < D / 4; ++c) {
       float4 x = src[c];
@@ -58,7 +70,7 @@ __global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileVi
     for (int e = lane; e < kKC * (D / 4); e += kQ) {
       const int row = e / (D / 4), c4 = e - row * (D / 4);
       if (row < cnt) {
-        const int64_t off = hoff + token_offset(tv, m0 + row);
+        const int64_t off = hoff + token_offset(tv, m0 + row, y0, x0);
         ((float4*)sK[wave][row])[c4] = ((const float4*)(k + off))[c4];
         ((float4*)sV[wave][row])[c4] = ((const float4*)(v + off))[c4];
       }
@@ -148,10 +160,9 @@ __global__ __launch_bounds__(kQ * kSplit) void attention_f32_kernel(const TileVi
 
 }  // namespace
 
-int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const float* q, const float* k,
-                         const float* v, float* out, const uint8_t* run_flag, hipStream_t s) {
+int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b, hipStream_t s) {
   if (head_dim != 64 && head_dim != 128) return SG_ERR_UNSUPPORTED;
-  dim3 grid((tv.N + kQ - 1) / kQ, heads);
+  if (b.n_tiles <= 0) return SG_OK;
   // K and V chunks of the 4 wavefronts (2 * 4 * 32 * D floats); the merge reuses them for the partial
   // outputs (4 * D * 64 floats, the same amount) and needs 2 * 4 * 64 floats more for the (m, l) pairs
   const size_t lds = ((size_t)2 * kSplit * kKC * head_dim + 2 * kSplit * kQ) * sizeof(float);
@@ -166,9 +177,24 @@ int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scal
     SG_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
   }
-  if (head_dim == 64) attention_f32_kernel<64><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
-  else attention_f32_kernel<128><<<grid, kQ * kSplit, lds, s>>>(tv, scale, q, k, v, out, run_flag);
-  SG_HIP_TRY(hipGetLastError());
+  for (int t0 = 0; t0 < b.n_tiles; t0 += kAttnTilesPerLaunch) {
+    const int n = (b.n_tiles - t0 < kAttnTilesPerLaunch) ? b.n_tiles - t0 : kAttnTilesPerLaunch;
+    AttnTable tab;
+    for (int i = 0; i < kAttnTilesPerLaunch; ++i) {
+      const bool in = i < n;
+      tab.q[i] = in ? b.q[t0 + i] : nullptr;
+      tab.k[i] = in ? b.k[t0 + i] : nullptr;
+      tab.v[i] = in ? b.v[t0 + i] : nullptr;
+      tab.out[i] = in ? b.out[t0 + i] : nullptr;
+      tab.y0[i] = (in && b.y0) ? b.y0[t0 + i] : 0;
+      tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
+    }
+    const dim3 grid((tv.N + kQ - 1) / kQ, heads, n);
+    const uint8_t* flags = b.run_flags ? b.run_flags + t0 : nullptr;
+    if (head_dim == 64) attention_f32_kernel<64><<<grid, kQ * kSplit, lds, s>>>(tv, scale, tab, flags);
+    else attention_f32_kernel<128><<<grid, kQ * kSplit, lds, s>>>(tv, scale, tab, flags);
+    SG_HIP_TRY(hipGetLastError());
+  }
   return SG_OK;
 }
 

@@ -126,11 +126,14 @@ __global__ __launch_bounds__(kFinalThreads) void gate_finalize_kernel(const doub
     __syncthreads();
   }
   if (threadIdx.x == 0) {
+    // Equation 7 reuses a tile only while its score is strictly below the threshold; the comparison is made
+    // in fp64 on the unrounded ratio, so a NaN score (NaN or Inf in the inputs) recomputes rather than
+    // reusing a stale cache.  The fp32 score is stored for reporting only.
     const bool cached = has_cache[tile] != 0;
-    float score = __builtin_inff();
-    if (cached && s_den[0] > 0.0) score = (float)(s_num[0] / s_den[0]);
-    scores[tile] = score;
-    recompute[tile] = (!cached || score >= threshold) ? 1 : 0;
+    double ratio = (double)__builtin_inff();
+    if (cached && !(s_den[0] == 0.0)) ratio = s_num[0] / s_den[0];
+    scores[tile] = (float)ratio;
+    recompute[tile] = (cached && ratio < (double)threshold) ? 0 : 1;
   }
 }
 

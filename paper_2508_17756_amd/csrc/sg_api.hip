@@ -39,23 +39,78 @@ static int validate(const sg_problem* p) {
   return SG_OK;
 }
 
-static TileView make_view(const sg_problem& p, int tile_row, int tile_col) {
+// Shape and strides shared by all tiles of p.
+static TileView make_view(const sg_problem& p, bool wrapped) {
   TileView tv;
   tv.stride_token = p.grid_stride_token;
   tv.stride_head = p.grid_stride_head;
   tv.T = p.T; tv.H = p.H; tv.W = p.W; tv.th = p.tile_h; tv.tw = p.tile_w;
   tv.N = p.T * p.tile_h * p.tile_w;
-  tv.base = ((int64_t)tile_row * p.stride_h * p.W + (int64_t)tile_col * p.stride_w) * p.grid_stride_token;
+  tv.wrapped = wrapped;
   return tv;
 }
 
-static int attention_dispatch(const sg_problem& p, const TileView& tv, const void* q, const void* k, const void* v,
-                              void* out, const uint8_t* run_flag, hipStream_t s) {
-  if (p.shift_h != 0 || p.shift_w != 0) return SG_ERR_UNSUPPORTED;   // wrapped windows are gathered first (sg_tile_slice)
-  if (p.dtype == SG_F32)
-    return launch_attention_f32(tv, p.heads, p.head_dim, p.scale, (const float*)q, (const float*)k, (const float*)v,
-                                (float*)out, run_flag, s);
-  return launch_attention_bf16(tv, p.heads, p.head_dim, p.scale, q, k, v, out, run_flag, s);
+// A packed tile is a canvas that is exactly one tile.
+static sg_problem packed_tile_problem(const sg_problem& p) {
+  sg_problem tp = p;
+  tp.H = p.tile_h; tp.W = p.tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
+  tp.stride_h = p.tile_h; tp.stride_w = p.tile_w;
+  tp.shift_h = tp.shift_w = 0;
+  tp.grid_stride_token = p.head_dim;
+  tp.grid_stride_head = (int64_t)p.T * p.tile_h * p.tile_w * p.head_dim;
+  return tp;
+}
+
+static int attention_launch(const sg_problem& p, const TileView& tv, const AttnBatch& b, hipStream_t s) {
+  if (p.dtype == SG_F32) return launch_attention_f32(tv, p.heads, p.head_dim, p.scale, b, s);
+  return launch_attention_bf16(tv, p.heads, p.head_dim, p.scale, b, s);
+}
+
+// Attention of the listed tiles of canvas tensors q, k, v, read in place, in as few launches as possible
+// (Algorithm 1: for all tiles of the partition).  Under a shifted partition the windows that cross a canvas
+// edge are read through the wrapping loader and the others as ordinary windows at their shifted origin.
+// tiles[i] = tile_row * n_tile_cols + tile_col;  out[i] = packed output of tiles[i].
+static int attention_canvas_tiles(const sg_problem& p, const void* q, const void* k, const void* v, const int* tiles,
+                                  int n, void* const* out, hipStream_t s) {
+  const size_t esz = p.dtype == SG_BF16 ? 2 : 4;
+  const void* qp[SG_MAX_TILES]; const void* kp[SG_MAX_TILES]; const void* vp[SG_MAX_TILES];
+  void* op[SG_MAX_TILES];
+  int32_t y0[SG_MAX_TILES], x0[SG_MAX_TILES];
+  for (int pass = 0; pass < 2; ++pass) {   // pass 0: windows inside the canvas; pass 1: windows that wrap
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+      const int tr = tiles[i] / p.n_tile_cols, tc = tiles[i] - tr * p.n_tile_cols;
+      const int y = (int)(((int64_t)tr * p.stride_h + p.shift_h) % p.H), x = (int)(((int64_t)tc * p.stride_w + p.shift_w) % p.W);
+      const bool wraps = y + p.tile_h > p.H || x + p.tile_w > p.W;
+      if (wraps != (pass == 1)) continue;
+      const size_t origin = wraps ? 0 : (size_t)(((int64_t)y * p.W + x) * p.grid_stride_token) * esz;
+      qp[m] = (const char*)q + origin; kp[m] = (const char*)k + origin; vp[m] = (const char*)v + origin;
+      op[m] = out[i];
+      y0[m] = y; x0[m] = x;
+      ++m;
+    }
+    if (!m) continue;
+    const AttnBatch b = {m, qp, kp, vp, op, pass ? y0 : nullptr, pass ? x0 : nullptr, nullptr};
+    const int st = attention_launch(p, make_view(p, pass == 1), b, s);
+    if (st != SG_OK) return st;
+  }
+  return SG_OK;
+}
+
+// Attention of packed tile inputs x[i] = [3][heads][T][tile_h][tile_w][d] (Q, K, V) in one launch; tiles whose
+// run flag (device) is 0 are skipped on the device.
+static int attention_packed_tiles(const sg_problem& p, const void* const* x, int n, void* const* out,
+                                  const uint8_t* run_flags, hipStream_t s) {
+  const sg_problem tp = packed_tile_problem(p);
+  const size_t part = (size_t)p.heads * p.T * p.tile_h * p.tile_w * p.head_dim * (p.dtype == SG_BF16 ? 2 : 4);
+  const void* qp[SG_MAX_TILES]; const void* kp[SG_MAX_TILES]; const void* vp[SG_MAX_TILES];
+  for (int i = 0; i < n; ++i) {
+    qp[i] = x[i];
+    kp[i] = (const char*)x[i] + part;
+    vp[i] = (const char*)x[i] + 2 * part;
+  }
+  const AttnBatch b = {n, qp, kp, vp, out, nullptr, nullptr, run_flags};
+  return attention_launch(tp, make_view(tp, false), b, s);
 }
 
 }  // namespace sg
@@ -95,7 +150,8 @@ int sg_tile_attention(const sg_problem* p, const void* q, const void* k, const v
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out_tile)) return SG_ERR_INVALID_ARG;
   if (tile_row < 0 || tile_row >= p->n_tile_rows || tile_col < 0 || tile_col >= p->n_tile_cols)
     return SG_ERR_INVALID_ARG;
-  return attention_dispatch(*p, make_view(*p, tile_row, tile_col), q, k, v, out_tile, nullptr, (hipStream_t)stream);
+  const int tile = tile_row * p->n_tile_cols + tile_col;
+  return attention_canvas_tiles(*p, q, k, v, &tile, 1, &out_tile, (hipStream_t)stream);
 }
 
 int sg_tile_blend(const sg_problem* p, const void* const* tile_out, void* grid_out, void* stream) {
@@ -164,32 +220,27 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   if (!io->tile_x) {  // canvas mode: every tile is recomputed from the shared canvas tensors
     if (!io->q || !io->k || !io->v) return SG_ERR_INVALID_ARG;
     if (!aligned16(io->q) || !aligned16(io->k) || !aligned16(io->v)) return SG_ERR_INVALID_ARG;
-    // With room for one packed tile input in the workspace every tile is gathered first (one plain copy) and
-    // attended in packed form: the packed loader is the fastest one, and wrapped (shifted) windows can only
-    // be read this way.  Without it the tiles are read in place.
+    // All tiles are read in place by one attention launch (windows of a shifted partition that cross a canvas
+    // edge go through the wrapping loader).  With room for one packed tile input in the workspace every tile is
+    // instead gathered first (one plain copy) and attended in packed form, tile by tile.
     const size_t packed_bytes = 3 * (size_t)tile_elems * esz;
     const bool gather = io->workspace && !(((uintptr_t)io->workspace) & 255u) && io->workspace_bytes >= packed_bytes;
-    if (!gather && (p->shift_h != 0 || p->shift_w != 0)) return io->workspace ? SG_ERR_WORKSPACE : SG_ERR_UNSUPPORTED;
-    sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
-    tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
-    tp.shift_h = tp.shift_w = 0;
-    tp.grid_stride_token = p->head_dim;
-    tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
-    const TileView packed_view = make_view(tp, 0, 0);
-    const void* src[3] = {io->q, io->k, io->v};
-    for (int tr = 0; tr < p->n_tile_rows; ++tr)
-      for (int tc = 0; tc < p->n_tile_cols; ++tc) {
-        void* out = io->cache_out[tr * p->n_tile_cols + tc];
-        if (gather) {
+    if (!gather) {
+      int tiles[SG_MAX_TILES];
+      for (int i = 0; i < n_tiles; ++i) tiles[i] = i;
+      st = attention_canvas_tiles(*p, io->q, io->k, io->v, tiles, n_tiles, io->cache_out, s);
+      if (st != SG_OK) return st;
+    } else {
+      const void* src[3] = {io->q, io->k, io->v};
+      for (int tr = 0; tr < p->n_tile_rows; ++tr)
+        for (int tc = 0; tc < p->n_tile_cols; ++tc) {
           st = launch_slice(*p, src, 3, tr, tc, io->workspace, s);
           if (st != SG_OK) return st;
-          const char* x = (const char*)io->workspace;
-          st = attention_dispatch(tp, packed_view, x, x + tile_elems * esz, x + 2 * tile_elems * esz, out, nullptr, s);
-        } else {
-          st = attention_dispatch(*p, make_view(*p, tr, tc), io->q, io->k, io->v, out, nullptr, s);
+          const void* x = io->workspace;
+          st = attention_packed_tiles(*p, &x, 1, &io->cache_out[tr * p->n_tile_cols + tc], nullptr, s);
+          if (st != SG_OK) return st;
         }
-        if (st != SG_OK) return st;
-      }
+    }
     return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);
   }
 
@@ -207,19 +258,8 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   st = launch_gate(io->tile_x, (const void* const*)io->cache_x, io->has_cache, n_tiles, 3 * tile_elems, p->dtype,
                    io->threshold, io->scores, io->recompute, io->workspace, s);
   if (st != SG_OK) return st;
-  // a packed tile is a canvas that is exactly one tile
-  sg_problem tp = *p;
-  tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
-  tp.shift_h = tp.shift_w = 0;
-  tp.grid_stride_token = p->head_dim;
-  tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
-  const TileView tv = make_view(tp, 0, 0);
-  for (int i = 0; i < n_tiles; ++i) {
-    const char* x = (const char*)io->tile_x[i];
-    st = attention_dispatch(tp, tv, x, x + tile_elems * esz, x + 2 * tile_elems * esz, io->cache_out[i],
-                            io->recompute + i, s);
-    if (st != SG_OK) return st;
-  }
+  st = attention_packed_tiles(*p, io->tile_x, n_tiles, io->cache_out, io->recompute, s);
+  if (st != SG_OK) return st;
   st = launch_cache_refresh(io->tile_x, io->cache_x, io->recompute, io->has_cache, n_tiles,
                             3 * tile_elems * (int64_t)esz, s);
   if (st != SG_OK) return st;
@@ -306,25 +346,14 @@ static int refine_step(const sg_problem* p, const sg_gain_step_io* io, const sg_
   if (st != SG_OK) return st;
   const int n_tiles = p->n_tile_rows * p->n_tile_cols;
   hipStream_t s = (hipStream_t)stream;
-  const size_t esz = p->dtype == SG_BF16 ? 2 : 4;
   const int64_t tile_elems = (int64_t)p->heads * p->T * p->tile_h * p->tile_w * p->head_dim;
 
   st = launch_gain_gate(io->tile_x, io->prev_x, io->state, n_tiles, 3 * tile_elems, p->dtype, io->threshold,
                         region ? region->thresholds : io->tile_thresholds, io->step_change, io->scores, io->recompute,
                         io->workspace, s);
   if (st != SG_OK) return st;
-  sg_problem tp = *p;   // a packed tile is a canvas that is exactly one tile
-  tp.H = p->tile_h; tp.W = p->tile_w; tp.n_tile_rows = tp.n_tile_cols = 1;
-  tp.shift_h = tp.shift_w = 0;
-  tp.grid_stride_token = p->head_dim;
-  tp.grid_stride_head = (int64_t)p->T * p->tile_h * p->tile_w * p->head_dim;
-  const TileView tv = make_view(tp, 0, 0);
-  for (int i = 0; i < n_tiles; ++i) {
-    const char* x = (const char*)io->tile_x[i];
-    st = attention_dispatch(tp, tv, x, x + tile_elems * esz, x + 2 * tile_elems * esz, io->out_cur[i],
-                            io->recompute + i, s);
-    if (st != SG_OK) return st;
-  }
+  st = attention_packed_tiles(*p, io->tile_x, n_tiles, io->out_cur, io->recompute, s);
+  if (st != SG_OK) return st;
   // the residual is taken against the Q part of the packed input unless the caller names a latent
   st = launch_gain_refresh(io->out_cur, io->out_prev, io->latent ? io->latent : io->tile_x, io->delta, io->recompute,
                            io->step_change, io->state, n_tiles, tile_elems, p->dtype, io->workspace, s);

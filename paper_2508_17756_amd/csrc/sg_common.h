@@ -14,25 +14,34 @@ int note_hip_error(hipError_t e);
     if (sg_e_ != hipSuccess) return sg::note_hip_error(sg_e_); \
   } while (0)
 
-// Canvas addressing of one tile, in elements, resolved on the host.
+// Shape and canvas addressing shared by the tiles of one attention call, in elements, resolved on the host.
 struct TileView {
-  int64_t base;          // element offset of tile token (0,0,0), head 0
   int64_t stride_token;  // elements between canvas tokens
   int64_t stride_head;
   int32_t T, H, W;       // canvas
   int32_t th, tw;        // tile
   int32_t N;             // T*th*tw tokens
+  bool wrapped;          // shifted partition: windows wrap around the canvas edges
+};
+
+// The tiles of one attention call.  For a fixed partition q[i], k[i], v[i] point at tile i's first token
+// (the tile origin is folded into the pointer); for wrapped windows they are the canvas tensors and
+// (y0[i], x0[i]) is the canvas position of tile i's first token.
+struct AttnBatch {
+  int n_tiles;
+  const void* const* q;      // host arrays of n_tiles device pointers
+  const void* const* k;
+  const void* const* v;
+  void* const* out;          // packed tile outputs
+  const int32_t* y0;         // host arrays, wrapped windows only (else nullptr)
+  const int32_t* x0;
+  const uint8_t* run_flags;  // device, n_tiles bytes: tiles with a 0 are skipped; nullptr = all tiles run
 };
 
 // Launchers (each validates nothing: the API layer has already done so).
-int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const float* q,
-                         const float* k, const float* v, float* out, const uint8_t* run_flag,
-                         hipStream_t s);
-int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const void* q,
-                          const void* k, const void* v, void* out, const uint8_t* run_flag,
-                          hipStream_t s);
-int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const void* q,
-                                  const void* k, const void* v, void* out, const uint8_t* run_flag,
+int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b, hipStream_t s);
+int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b, hipStream_t s);
+int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, float scale, const AttnBatch& b,
                                   hipStream_t s);
 int launch_blend(const sg_problem& p, const void* const* tile_out, void* grid_out, const void* latent, float c_latent,
                  float c_noise, hipStream_t s);

@@ -82,10 +82,10 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_gain_refresh(arr, arr, arr, None, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_gain_refresh(arr, arr, arr, arr, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 16, None) == sg.SG_ERR_WORKSPACE
     assert lib.sg_denoise_step_gain(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG
-    # shifted partitions: gathered, not read in place
+    # shifted partitions
     ps = sg.make_problem(CONFIGS["tiny_f32"], shift=(3, 5))
     assert sg.sg_problem_validate(ps) == sg.SG_OK
-    assert lib.sg_tile_attention(ctypes.byref(ps), 16, 16, 16, 0, 0, 16, None) == sg.SG_ERR_UNSUPPORTED
+    assert lib.sg_tile_attention(ctypes.byref(ps), 16, 16, 16, 2, 0, 16, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_tile_slice(ctypes.byref(ps), arr, 4, 0, 0, 256, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_tile_slice(ctypes.byref(ps), arr, 2, 2, 0, 256, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_tile_blend_update(ctypes.byref(ps), arr, None, 1.0, 0.1, 256, None) == sg.SG_ERR_INVALID_ARG

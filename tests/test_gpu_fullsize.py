@@ -28,7 +28,14 @@ def _oracle_rows(g, qkv, tr, tc, heads, rows):
     return out
 
 
+def _four_heads(g, salt):
+    """Head 0, the last head and two more that move with `salt`."""
+    mid = {1 + (5 * salt + 3) % (g.heads - 2), 1 + (11 * salt + 7) % (g.heads - 2)} if g.heads > 3 else set()
+    return sorted({0, g.heads - 1} | mid)
+
+
 def _check_tile(g, qkv, tr, tc, got, heads, n_rows, seed):
+    """n_rows sampled query rows (the same rows for each of `heads`) of one tile against the oracle, pooled."""
     rows = sample_rows(seed, g.tile_tokens, n_rows)
     ref = _oracle_rows(g, qkv, tr, tc, heads, rows)
     gt = got.reshape(g.heads, g.tile_tokens, g.head_dim)
@@ -86,6 +93,7 @@ def _end_to_end_tokens(g, qkv, canvas, head, tokens):
     from dataclasses import replace
     g1 = replace(g, heads=1, T=1)
     kv_cache = {}
+    num = den = 0.0
     for (t, y, x) in tokens:
         tiles = []
         for tr in range(g.n_tile_rows):
@@ -104,37 +112,46 @@ def _end_to_end_tokens(g, qkv, canvas, head, tokens):
         ref = oracle.blend(tiles, g1)[0, 0, y, x, :]
         got = to_f64(canvas[head, t, y, x, :])
         assert np.isfinite(ref).all()
-        ma = float(np.abs(got - ref).max())
-        rl = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
-        assert ma <= BF16_MAX_ABS and rl <= 4 * BF16_REL_L2, (t, y, x, ma, rl)   # 128 values: the L2 bound is a statistic, allow slack
+        assert float(np.abs(got - ref).max()) <= BF16_MAX_ABS, (t, y, x)
+        num += float(((got - ref) ** 2).sum())
+        den += float((ref ** 2).sum())
         kv_cache = {k: v for k, v in kv_cache.items() if k in list(kv_cache)[-2:]}   # bound host memory
+    rl = (num / den) ** 0.5                 # one relative L2 over all sampled tokens, at the stated tolerance
+    assert rl <= BF16_REL_L2, rl
+    return rl
 
 
-@pytest.mark.parametrize("name,rows_per_tile", [("canvas2k_bf16", 32), ("canvas4k_bf16", 16)])
+@pytest.mark.parametrize("name,rows_per_tile", [("canvas2k_bf16", 40), ("canvas4k_bf16", 36)])
 def test_config3_and_4_tiled_step(name, rows_per_tile):
+    """Every tile of the step: rows_per_tile sampled query rows in each of four heads (head 0, the last head and two
+    that move with the tile), i.e. 160 / 144 (head, row) pairs per tile, each set pooled at the stated tolerance."""
     g = CONFIGS[name]
     qkv = _device_canvas(g)
     tiles = [torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
     canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
     sg.sg_denoise_step_tiled(sg.make_problem(g), canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2])
     torch.cuda.synchronize()
-    for i in range(g.n_tiles):            # every tile: one head, sampled rows incl. the ragged tail
+    for i in range(g.n_tiles):            # every tile: four heads, sampled rows incl. the ragged tail
         tr, tc = divmod(i, g.n_tile_cols)
-        _check_tile(g, qkv, tr, tc, tiles[i], [(7 * i + 3) % g.heads], rows_per_tile, g.seed + i)
+        _check_tile(g, qkv, tr, tc, tiles[i], _four_heads(g, i), rows_per_tile, g.seed + i)
     _blend_plane_check(g, tiles, canvas, [(0, 0), (g.heads - 1, g.T - 1), (17, 9)])
     # end to end against the oracle alone: a corner (one tile), an edge of an overlap, the most covered
     # region, the last token
     oh, ow = g.tile_h - g.stride_h, g.tile_w - g.stride_w
     toks = [(0, 0, 0), (g.T // 2, g.stride_h, g.stride_w + ow // 2), (g.T - 1, g.H - 1, g.W - 1)]
     toks.append((3, 2 * g.stride_h + 1, g.stride_w + 1) if name == "canvas2k_bf16" else (3, g.stride_h + oh - 1, 2 * g.stride_w + 3))
+    toks += [(g.T - 2, g.stride_h - 1, g.W - g.stride_w), (7, g.H - g.stride_h, 1), (11, g.tile_h - 1, g.tile_w - 1),
+             (1, g.H // 2, g.W // 2)]
     _end_to_end_tokens(g, qkv, canvas, 17, toks)
+    _end_to_end_tokens(g, qkv, canvas, 0, toks[:3])
+    _end_to_end_tokens(g, qkv, canvas, g.heads - 1, toks[3:6])
 
 
 def test_config5_gated_steps():
     """10 denoising steps over the 4K grid with per-tile inputs; eps per (step, tile) from the host
     table.  Decisions must equal (eps == 0.1) for k >= 1 (scores sit >= 0.015 away from the
-    threshold), gate scores are checked in fp64 on two tiles of three steps, attention rows on the
-    recomputed tiles of three steps, the blend on whole planes at the last step."""
+    threshold), gate scores are checked in fp64 on two tiles of three steps, attention rows (four heads x 32
+    rows) on three recomputed tiles of every step, the blend on whole planes at the last step."""
     g = CONFIGS["canvas4k_gate_bf16"]
     n, steps = g.n_tiles, g.steps
     qkv = _device_canvas(g)
@@ -185,11 +202,11 @@ def test_config5_gated_steps():
                 if abs(ref - thr) > 1e-4:
                     assert r[i] == (ref >= thr)
         n_recomputed += int(r.sum())
+        done = [i for i in range(n) if r[i]]
+        for i in (done[:2] + done[-1:] if len(done) > 2 else done):      # every step: attention rows of recomputed tiles
+            x = tile_x[i]
+            _check_tile(gt, [x[0], x[1], x[2]], 0, 0, cache_out[i], _four_heads(g, i + k), 32, g.seed + 31 * k + i)
         if k in (0, 1, steps - 1):
-            done = [i for i in range(n) if r[i]][:3]
-            for i in done:
-                x = tile_x[i]
-                _check_tile(gt, [x[0], x[1], x[2]], 0, 0, cache_out[i], [(5 * i + k) % g.heads], 8, g.seed + 31 * k + i)
             for i in range(n):                            # recomputed tiles hold the new input, the others the old one
                 if r[i]:
                     assert torch.equal(cache_x[i][0, 0, 0, 0], tile_x[i][0, 0, 0, 0])

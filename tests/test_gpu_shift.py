@@ -157,13 +157,47 @@ def test_canvas_step_gathers_tiles_when_given_a_workspace(dtype, shift):
         canvas2 = torch.empty(g.grid_shape, dtype=td, device="cuda")
         sg.sg_denoise_step_tiled(p, canvas2, tiles2, q=qkv[0], k=qkv[1], v=qkv[2])
         assert torch.equal(canvas2, canvas) and all(torch.equal(a, b) for a, b in zip(tiles, tiles2))
-    else:
-        with pytest.raises(sg.SgError) as e:                              # wrapped windows need the workspace
-            sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2])
-        assert e.value.status == sg.SG_ERR_UNSUPPORTED
-        with pytest.raises(sg.SgError) as e:
-            sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2], workspace=ws[:1024])
-        assert e.value.status == sg.SG_ERR_WORKSPACE
+    else:                                                                  # wrapped windows read in place: same numbers
+        tiles2 = [torch.full(g.tile_shape, float("nan"), dtype=td, device="cuda") for _ in range(g.n_tiles)]
+        canvas2 = torch.full(g.grid_shape, float("nan"), dtype=td, device="cuda")
+        sg.sg_denoise_step_tiled(p, canvas2, tiles2, q=qkv[0], k=qkv[1], v=qkv[2])
+        assert torch.equal(canvas2, canvas) and all(torch.equal(a, b) for a, b in zip(tiles, tiles2))
+
+
+WRAP_CASES = [
+    # name, T, H, W, th, tw, sh, sw, heads, d, dtype, token_major, shift
+    ("bf16_w16_rows_and_cols", 3, 20, 40, 12, 16, 8, 8, 2, 128, "bf16", False, (5, 9)),      # N = 576; tile width 16
+    ("bf16_w13_odd", 2, 17, 21, 9, 13, 8, 8, 2, 128, "bf16", False, (16, 20)),               # odd width: per-lane walk either way
+    ("bf16_paper_nonoverlap", 2, 12, 24, 6, 8, 6, 8, 2, 128, "bf16", False, (1, 1)),         # the paper's partition, shift tile/…
+    ("bf16_token_major", 2, 12, 24, 6, 8, 6, 8, 3, 128, "bf16", True, (7, 3)),
+    ("bf16_d64", 2, 12, 24, 6, 8, 6, 8, 2, 64, "bf16", False, (2, 21)),                      # head_dim 64 in place: register-staged kernel
+    ("f32_d64", 3, 16, 16, 10, 10, 6, 6, 2, 64, "f32", False, (3, 11)),
+    ("f32_d128_token_major", 2, 9, 11, 5, 6, 4, 5, 2, 128, "f32", True, (8, 10)),
+]
+
+
+@pytest.mark.parametrize("case", WRAP_CASES, ids=[c[0] for c in WRAP_CASES])
+def test_attention_reads_a_wrapped_window_in_place(case):
+    """sg_tile_attention under a shifted partition (Algorithm 1 "Shift" + "SliceTile"): every tile, whether its
+    window wraps around a canvas edge or not, against the oracle's attention of the oracle's shifted slice."""
+    name, T, H, W, th, tw, sh, sw, heads, d, dtype, token_major, shift = case
+    g = _geom(name, T, H, W, th, tw, sh, sw, heads, d, dtype, 71)
+    td = torch_dtype(dtype)
+    qkv = [randn_tensor(g.grid_shape, dtype, g.seed + 7 * s).cuda() for s in range(3)]
+    dev = [t.permute(1, 2, 3, 0, 4).contiguous() for t in qkv] if token_major else qkv
+    p = sg.make_problem(g, token_major=token_major, shift=shift)
+    wrapped = 0
+    for tr in range(g.n_tile_rows):
+        for tc in range(g.n_tile_cols):
+            out = torch.full(g.tile_shape, float("nan"), dtype=td, device="cuda")
+            sg.sg_tile_attention(p, dev[0], dev[1], dev[2], tr, tc, out)
+            Q, K, V = (oracle.slice_tile_shifted(to_f64(t), g, tr, tc, *shift) for t in qkv)
+            ref = np.stack([oracle.attention(Q[a].reshape(-1, d), K[a].reshape(-1, d), V[a].reshape(-1, d), g.scale)
+                            for a in range(g.heads)]).reshape(g.tile_shape)
+            assert_close(to_f64(out), ref, dtype, f"{name} tile {tr},{tc}")
+            y, x = (tr * sh + shift[0]) % H, (tc * sw + shift[1]) % W
+            wrapped += int(y + th > H or x + tw > W)
+    assert 0 < wrapped < g.n_tiles or g.n_tiles == 1      # the case exercises both kinds of window
 
 
 def _random_tilings(count, seed):

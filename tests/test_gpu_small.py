@@ -274,6 +274,23 @@ def test_gate_edge_cases():
     _gate([], [], [], 0.05)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("where,bad", [("cur", float("nan")), ("cached", float("nan")), ("cur", float("inf")),
+                                       ("cached", float("inf"))])
+def test_gate_nan_or_inf_input_recomputes(dtype, where, bad):
+    """A NaN or Inf anywhere in a tile's input or cache must not leave the stale cache in use (Equation 7 reuses
+    only strictly below the threshold); the oracle takes the same decisions."""
+    n = 3
+    cached = [randn_tensor((8192 + 24,), dtype, 1300 + i).cuda() for i in range(n)]
+    cur = [perturb_(c.clone(), 0.01, 1400 + i) for i, c in enumerate(cached)]      # all three would reuse
+    (cur if where == "cur" else cached)[1][4321] = bad
+    s, r = _gate(cur, cached, [1] * n, 0.05)
+    so, ro = oracle.cache_gate([to_f64(t) for t in cur], [to_f64(t) for t in cached], [1] * n, float(np.float32(0.05)))
+    assert list(r.astype(bool)) == list(ro) == [False, True, False]
+    assert not (s[1] < 0.05) and not (so[1] < 0.05)
+    assert abs(s[0] - so[0]) <= 2e-6 and abs(s[2] - so[2]) <= 2e-6
+
+
 def test_gate_many_tiles():
     n = 70                                            # more than one launch's worth of pointers
     cached = [randn_tensor((2048,), "bf16", 1000 + i).cuda() for i in range(n)]
@@ -331,6 +348,50 @@ def test_step_cached_mode_bf16_three_steps(d):
         assert_close(to_f64(canvas), ref_canvas, "bf16", f"step {step}")
         for i in range(n):                       # cache holds exactly the last recomputed input
             assert np.array_equal(to_f64(cache_x[i]).ravel(), state.cache_x[i])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_cached_mode_many_tiles_one_launch_skips_on_the_device(dtype):
+    """40 packed tiles (more than one launch's table of 32) through the cached step: the attention launches number
+    only the tiles the gate flags, whichever they are.  Reused tiles must keep their cached output bit for bit,
+    recomputed ones must match the oracle; the flagged sets straddle the two launches unevenly."""
+    d = 128 if dtype == "bf16" else 64
+    g = _geom("many", 1, 18, 23, 6, 5, 3, 2, 2, d, dtype, 67)            # 5 x 10 = 50 tiles, N = 30 (one ragged block)
+    n = g.n_tiles
+    assert n == 50
+    td = torch_dtype(dtype)
+    tile_x = [randn_tensor((3,) + g.tile_shape, dtype, 4000 + i).cuda() for i in range(n)]
+    cache_x = [torch.zeros_like(t) for t in tile_x]
+    cache_out = [torch.zeros(g.tile_shape, dtype=td, device="cuda") for _ in range(n)]
+    has_cache = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    rec = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    canvas = torch.empty(g.grid_shape, dtype=td, device="cuda")
+    p = sg.make_problem(g)
+    patterns = [None,
+                [i in (0, 31, 32, 49) for i in range(n)],                 # first and last slot of both launches
+                [i >= 33 for i in range(n)],                              # first launch entirely skipped
+                [False] * n]                                              # nothing runs
+    for step, pat in enumerate(patterns):
+        if pat is not None:
+            for i in range(n):
+                perturb_(tile_x[i], 0.1 if pat[i] else 0.001, 5000 + 100 * step + i)
+        before = [t.clone() for t in cache_out]
+        sg.sg_denoise_step_tiled(p, canvas, cache_out, tile_x=tile_x, cache_x=cache_x, has_cache=has_cache,
+                                 threshold=0.05, scores=scores, recompute=rec, workspace=ws)
+        torch.cuda.synchronize()
+        want = [True] * n if pat is None else pat
+        assert list(rec.cpu().numpy().astype(bool)) == want, step
+        for i in range(n):
+            if not want[i]:
+                assert torch.equal(cache_out[i], before[i]), (step, i)
+            elif i in (0, 31, 32, 33, 49):
+                Q, K, V = (to_f64(tile_x[i][j]) for j in range(3))
+                ref = np.stack([oracle.attention(Q[a].reshape(-1, d), K[a].reshape(-1, d), V[a].reshape(-1, d), g.scale)
+                                for a in range(g.heads)]).reshape(g.tile_shape)
+                assert_close(to_f64(cache_out[i]), ref, dtype, f"step {step} tile {i}")
+        assert_close(to_f64(canvas), oracle.blend([to_f64(t) for t in cache_out], g), dtype, f"canvas step {step}")
 
 
 # ------------------------------------------------------------------ error paths reach no kernel

@@ -44,6 +44,18 @@ def test_no_cache_or_zero_cache_recomputes():
     assert r.all() and np.isinf(s).all()
 
 
+@pytest.mark.parametrize("where,bad", [("cur", np.nan), ("cached", np.nan), ("cur", np.inf), ("cached", np.inf)])
+def test_nan_or_inf_input_never_reuses(where, bad):
+    """Equation 7 reuses only while the score is strictly below the threshold: a score that is NaN or +inf is not."""
+    xc = _rand(64, 6)
+    x = xc * 1.001                       # would reuse (score 0.001) without the bad element
+    assert not oracle.cache_gate([x], [xc], [True], 0.05)[1][0]
+    x, xc = x.copy(), xc.copy()
+    (x if where == "cur" else xc)[17] = bad
+    s, r = oracle.cache_gate([x], [xc], [True], 0.05)
+    assert r[0] and not (s[0] < 0.05)
+
+
 def test_brute_force_small():
     a, b = _rand(257, 4), _rand(257, 5)
     num = sum(abs(float(x) - float(y)) for x, y in zip(a, b))

@@ -28,8 +28,10 @@ MUTATIONS = [
     ("gate_denominator_is_current", G, 'den = np.abs(b).sum()\n    return float("inf")', 'den = np.abs(a).sum()\n    return float("inf")'),
     ("gate_l2_norm", G, "num = np.abs(a - b).sum()\n    den = np.abs(b).sum()",
      "num = np.sqrt(((a - b) ** 2).sum())\n    den = np.sqrt((b ** 2).sum())"),
-    ("gate_tie_reuses", G, "recompute.append(bool((not hc) or s >= float(threshold)))",
-     "recompute.append(bool((not hc) or s > float(threshold)))"),
+    ("gate_tie_reuses", G, "recompute.append(not (bool(hc) and s < float(threshold)))",
+     "recompute.append(not (bool(hc) and s <= float(threshold)))"),
+    ("gate_nan_score_reuses", G, "recompute.append(not (bool(hc) and s < float(threshold)))",
+     "recompute.append(bool((not hc) or s >= float(threshold)))"),
     ("gain_tie_reuses", N, "recompute[i] = not (scores[i] < float(thresholds[i]))",
      "recompute[i] = not (scores[i] <= float(thresholds[i]))"),
     ("path_length_not_accumulated", N, "state.path_len[i] += d[i]", "state.path_len[i] = d[i]"),
