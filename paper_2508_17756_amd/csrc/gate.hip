@@ -204,8 +204,40 @@ __global__ __launch_bounds__(kFinalThreads) void gain_gate_finalize_kernel(
 constexpr int kRefreshTilesPerLaunch = 32;
 // Measured on the 4K sizes: unroll 1-8 and 1-4 workgroups per compute unit all land within 4.4-5.1 TB/s (the
 // pass writes 40-25 % of its bytes and runs at the device's copy rate); 2 and 1 were the best pair.
+// Measured at the 4K sizes (20 tiles, half recomputed): equal contiguous slabs per workgroup with strided 16-byte
+// halves 4.9 TB/s; chunks dealt round-robin 5.1; round-robin chunks with the lanes exchanging halves (below) 5.35,
+// the plain copy rate of the same device.  Unroll 1 / 4 and 2 - 4 workgroups per compute unit are no faster.
 constexpr int kRefreshUnroll = 2;
 constexpr int kRefreshBlocksPerCu = 1;
+
+// The eight fp32 residuals of a thread's 16-byte bf16 vector are 32 contiguous bytes, so a wavefront's 64 vectors
+// map to one 2 KiB run of delta.  Accessed as "every lane its own two 16-byte halves" each instruction would touch
+// only half of every line (measured: 6 % more bytes written than the algorithmic amount).  Instead the lanes
+// exchange halves through the cross-lane network so that one instruction covers the first contiguous KiB of the run
+// (lane L: 16-byte slot L) and the other the second (slot 64 + L).  Slot s holds half (s & 1) of lane s >> 1.
+__device__ __forceinline__ u32x4 lane_gather(const u32x4 v, const int src_lane) {
+  u32x4 r;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) r[c] = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)v[c]);
+  return r;
+}
+// own halves (d0, d1) -> the two contiguous slots this lane stores (slot L and slot 64 + L)
+__device__ __forceinline__ void halves_to_slots(const u32x4 d0, const u32x4 d1, u32x4& lo, u32x4& hi) {
+  const int lane = threadIdx.x & 63;
+  const u32x4 a0 = lane_gather(d0, lane >> 1), a1 = lane_gather(d1, lane >> 1);
+  const u32x4 b0 = lane_gather(d0, 32 + (lane >> 1)), b1 = lane_gather(d1, 32 + (lane >> 1));
+  lo = (lane & 1) ? a1 : a0;
+  hi = (lane & 1) ? b1 : b0;
+}
+// the two contiguous slots this lane loaded (slot L and slot 64 + L) -> own halves (slots 2L and 2L + 1)
+__device__ __forceinline__ void slots_to_halves(const u32x4 lo, const u32x4 hi, u32x4& d0, u32x4& d1) {
+  const int lane = threadIdx.x & 63;
+  const int s0 = (2 * lane) & 63, s1 = (2 * lane + 1) & 63;
+  const u32x4 l0 = lane_gather(lo, s0), h0 = lane_gather(hi, s0);
+  const u32x4 l1 = lane_gather(lo, s1), h1 = lane_gather(hi, s1);
+  d0 = (lane < 32) ? l0 : h0;
+  d1 = (lane < 32) ? l1 : h1;
+}
 
 // one 16-byte vector of outputs: O = I + delta (delta in fp32: two vectors for bf16 tensors, one for fp32)
 template <int DT>
@@ -250,7 +282,7 @@ struct GainPtrs {
 //   recomputed tile: delta_c = O_t - I_t (fp32) is stored and, if a previous output exists, the sums of
 //                    ||O_t - O_{t-1}||_1 and ||O_{t-1}||_1 are taken in the same pass (O_t is read once);
 //   reused tile:     O_t = I_t + delta_c is written (Residual Approximation).
-// Same streaming layout as the gate: one workgroup per compute unit, equal contiguous slabs per tile.
+// One workgroup per compute unit; the workgroups walk each tile's buffers together, chunk by chunk.
 // delta is kept in fp32: its magnitude follows the latent's and can exceed the output's by orders, so
 // the output's storage type would lose O_c.
 template <int DT>
@@ -260,30 +292,47 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
   constexpr int kPerVec = (DT == SG_BF16) ? 8 : 4;
   const int blk = blockIdx.x, n_blk = gridDim.x;
   const int64_t n_vec = elems / kPerVec;
-  const int64_t per_blk = (n_vec + n_blk - 1) / n_blk;
-  const int64_t v0 = (int64_t)blk * per_blk;
-  const int64_t v1 = (v0 + per_blk < n_vec) ? v0 + per_blk : n_vec;
+  // chunks of kRefreshUnroll * kThreads vectors are dealt round-robin to the workgroups, so at any moment the
+  // whole device works on one contiguous window of every stream; the ragged rest (fewer vectors than a chunk)
+  // goes to one workgroup, vector by vector without the lane exchange
+  constexpr int64_t kChunk = (int64_t)kRefreshUnroll * kThreads;
+  const int64_t n_chunks = n_vec / kChunk, main_end = n_chunks * kChunk;
+  const int64_t first = (int64_t)blk * kChunk + threadIdx.x, step = (int64_t)n_blk * kChunk;
+  const int64_t tail_first = (blk == (int)(n_chunks % n_blk)) ? main_end + threadIdx.x : n_vec, tail_end = n_vec;
+  auto main_ok = [&](int64_t i) __attribute__((always_inline)) { return i - threadIdx.x < main_end; };
+  auto tail_begin = [&](int64_t) __attribute__((always_inline)) { return tail_first; };
   for (int tile = 0; tile < n_tiles; ++tile) {
     double* out = partial + ((size_t)(tile0 + tile) * kGateSlots + blk * kWavesPerBlock) * 2;
     u32x4* __restrict__ oc = (u32x4*)ptrs.out_cur[tile];
     const u32x4* __restrict__ lat = (const u32x4*)ptrs.latent[tile];
     u32x4* __restrict__ dl = (u32x4*)ptrs.delta[tile];
     if (!recompute[tile0 + tile]) {   // reuse: O_t = I_t + delta_c
-      int64_t i = v0 + threadIdx.x;
-      for (; i + (kRefreshUnroll - 1) * kThreads < v1; i += kRefreshUnroll * kThreads) {
+      int64_t i = first;
+      for (; main_ok(i); i += step) {
         u32x4 l[kRefreshUnroll], d0[kRefreshUnroll], d1[kRefreshUnroll];
 #pragma unroll
         for (int u = 0; u < kRefreshUnroll; ++u) {
           const int64_t j = i + u * kThreads;
           l[u] = __builtin_nontemporal_load(lat + j);
-          if (DT == SG_BF16) { d0[u] = __builtin_nontemporal_load(dl + 2 * j); d1[u] = __builtin_nontemporal_load(dl + 2 * j + 1); }
-          else d0[u] = __builtin_nontemporal_load(dl + j);
+          if (DT == SG_BF16) {   // j - lane is the wavefront's first vector: its delta run starts at 2 (j - lane)
+            const int64_t w0 = 2 * (j - (threadIdx.x & 63)) + (threadIdx.x & 63);
+            d0[u] = __builtin_nontemporal_load(dl + w0);
+            d1[u] = __builtin_nontemporal_load(dl + w0 + 64);
+          } else {
+            d0[u] = __builtin_nontemporal_load(dl + j);
+          }
         }
 #pragma unroll
-        for (int u = 0; u < kRefreshUnroll; ++u)
+        for (int u = 0; u < kRefreshUnroll; ++u) {
+          if (DT == SG_BF16) {
+            u32x4 h0, h1;
+            slots_to_halves(d0[u], d1[u], h0, h1);
+            d0[u] = h0; d1[u] = h1;
+          }
           __builtin_nontemporal_store(residual_apply<DT>(l[u], d0[u], d1[u]), oc + i + u * kThreads);
+        }
       }
-      for (; i < v1; i += kThreads) {
+      for (i = tail_begin(i); i < tail_end; i += kThreads) {
         const u32x4 l = __builtin_nontemporal_load(lat + i);
         u32x4 d0, d1 = {0, 0, 0, 0};
         if (DT == SG_BF16) { d0 = __builtin_nontemporal_load(dl + 2 * i); d1 = __builtin_nontemporal_load(dl + 2 * i + 1); }
@@ -297,8 +346,8 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
     const bool sums = has_prev[tile0 + tile] != 0;
     const u32x4* __restrict__ op = (const u32x4*)ptrs.out_prev[tile];
     float num0 = 0.f, den0 = 0.f, num1 = 0.f, den1 = 0.f;
-    int64_t i = v0 + threadIdx.x;
-    for (; i + (kRefreshUnroll - 1) * kThreads < v1; i += kRefreshUnroll * kThreads) {
+    int64_t i = first;
+    for (; main_ok(i); i += step) {
       u32x4 a[kRefreshUnroll], l[kRefreshUnroll], b[kRefreshUnroll];
 #pragma unroll
       for (int u = 0; u < kRefreshUnroll; ++u) {
@@ -313,11 +362,18 @@ __global__ __launch_bounds__(kThreads) void gain_refresh_kernel(GainPtrs ptrs, c
         if (sums) { if (u & 1) accum_vec<DT>(a[u], b[u], num1, den1); else accum_vec<DT>(a[u], b[u], num0, den0); }
         u32x4 d0, d1;
         residual_take<DT>(a[u], l[u], d0, d1);
-        if (DT == SG_BF16) { __builtin_nontemporal_store(d0, dl + 2 * j); __builtin_nontemporal_store(d1, dl + 2 * j + 1); }
-        else __builtin_nontemporal_store(d0, dl + j);
+        if (DT == SG_BF16) {
+          u32x4 lo, hi;
+          halves_to_slots(d0, d1, lo, hi);
+          const int64_t w0 = 2 * (j - (threadIdx.x & 63)) + (threadIdx.x & 63);
+          __builtin_nontemporal_store(lo, dl + w0);
+          __builtin_nontemporal_store(hi, dl + w0 + 64);
+        } else {
+          __builtin_nontemporal_store(d0, dl + j);
+        }
       }
     }
-    for (; i < v1; i += kThreads) {
+    for (i = tail_begin(i); i < tail_end; i += kThreads) {
       const u32x4 a = __builtin_nontemporal_load((const u32x4*)oc + i);
       const u32x4 l = __builtin_nontemporal_load(lat + i);
       if (sums) accum_vec<DT>(a, __builtin_nontemporal_load(op + i), num0, den0);

@@ -12,7 +12,7 @@ import oracle
 import paper_2508_17756_amd as sg
 from synthetic import CONFIGS, TileGeometry, randn_tensor, torch_dtype, scaled_down, eps_table, perturb_
 from gpu_util import (to_f64, errors, assert_close, canvas_qkv, gpu_tile_attention,
-                      oracle_tile_attention_full)
+                      oracle_tile_attention_full, BF16_MAX_ABS, BF16_REL_L2)
 
 pytestmark = pytest.mark.gpu
 
@@ -152,6 +152,25 @@ def test_attention_bf16_large_logits_and_constant_v():
     vc = torch.full_like(v, 0.75)
     got = gpu_tile_attention(g, q, k, vc, 0, 0)
     assert float((got.float() - 0.75).abs().max()) <= 0.75 * 2 ** -7
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("sigma", [1.0, 1.5, 2.0])
+def test_attention_bf16_wider_inputs_keep_the_tolerance(sigma, d):
+    """Q and K ~ N(0, sigma^2) with uncorrelated keys: the kernel multiplies Q by scale * log2(e) and rounds it to bf16
+    once more before the score products, an error that grows with |q| |k| and does not cancel in the normalisation.
+    At sigma = 2 the logits reach about +-15; the result must still be within the bf16 tolerance of the oracle."""
+    g = _geom("wide", 6, 12, 16, 12, 16, 12, 16, 2, d, "bf16", 47)       # N = 1152: 18 key stages
+    q, k, v = canvas_qkv(g)
+    q = (q.float() * sigma).to(torch.bfloat16)
+    k = (k.float() * sigma).to(torch.bfloat16)
+    got = gpu_tile_attention(g, q, k, v, 0, 0)
+    ref = oracle_tile_attention_full(g, q, k, v, 0, 0)
+    ma, rl = errors(to_f64(got), ref)
+    print(f"sigma={sigma} d={d}: max_abs={ma:.3e} rel_l2={rl:.3e} max|ref|={np.abs(ref).max():.2f}")
+    # the softmax concentrates, outputs reach several units: the absolute bound of the N(0,1) workloads (2e-2, there 3
+    # times the largest output) scales with the output's magnitude, the relative L2 bound is the stated one
+    assert rl <= BF16_REL_L2 and ma <= BF16_MAX_ABS * max(1.0, float(np.abs(ref).max())), (ma, rl)
 
 
 @pytest.mark.parametrize("d", [128, 64])
