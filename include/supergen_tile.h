@@ -203,7 +203,7 @@ typedef struct sg_step_io {
   uint8_t* recompute;     /* cached mode: device, n_tiles bytes (out)                                           */
   void* grid_out;         /* device, canvas tensor (out)                                                        */
   void* workspace;        /* cached mode: device scratch, sg_workspace_bytes(n_tiles); canvas mode: optional,   */
-                          /* room for one packed tile input (see sg_denoise_step_tiled)                         */
+                          /* room for one or more packed tile inputs (see sg_denoise_step_tiled)                */
   size_t workspace_bytes;
 } sg_step_io;
 
@@ -213,8 +213,9 @@ typedef struct sg_step_io {
  *   canvas mode: cache_out[i] = attention(tile i of q, k, v) for every tile; grid_out = Fuse.  All
  *     tiles are read in place and attended by one launch (two under a shifted partition: the windows
  *     that wrap around a canvas edge and those that do not).  If `workspace` (256-byte aligned) holds
- *     at least one packed tile input, 3 * heads * T * tile_h * tile_w * head_dim elements, every tile
- *     is instead gathered into it (sg_tile_slice) and attended in packed form, tile by tile.
+ *     G >= 1 packed tile inputs (each 3 * heads * T * tile_h * tile_w * head_dim elements, rounded up
+ *     to 256 bytes), the tiles are instead gathered into it G at a time (sg_tile_slice) and every group
+ *     is attended in packed form by one launch; with room for all tiles this is the fastest form.
  *   cached mode: gate every tile on tile_x[i] against cache_x[i]; for the tiles to recompute
  *     cache_out[i] = attention(tile_x[i]), cache_x[i] = tile_x[i], has_cache[i] = 1; reused
  *     tiles keep their cache entries untouched (drift stays measured from the last recomputed

@@ -221,25 +221,32 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
     if (!io->q || !io->k || !io->v) return SG_ERR_INVALID_ARG;
     if (!aligned16(io->q) || !aligned16(io->k) || !aligned16(io->v)) return SG_ERR_INVALID_ARG;
     // All tiles are read in place by one attention launch (windows of a shifted partition that cross a canvas
-    // edge go through the wrapping loader).  With room for one packed tile input in the workspace every tile is
-    // instead gathered first (one plain copy) and attended in packed form, tile by tile.
-    const size_t packed_bytes = 3 * (size_t)tile_elems * esz;
-    const bool gather = io->workspace && !(((uintptr_t)io->workspace) & 255u) && io->workspace_bytes >= packed_bytes;
-    if (!gather) {
+    // edge go through the wrapping loader).  With room for G >= 1 packed tile inputs in the workspace the tiles
+    // are instead gathered G at a time (plain copies) and each group is attended in packed form by one launch:
+    // a packed tile spans a fraction of the canvas' address range, which the streaming loads reward.
+    const size_t packed_bytes = ((3 * (size_t)tile_elems * esz + 255) / 256) * 256;   // per tile, keeps every copy aligned
+    const bool aligned_ws = io->workspace && !(((uintptr_t)io->workspace) & 255u);
+    const size_t room = aligned_ws ? io->workspace_bytes / packed_bytes : 0;
+    if (room == 0) {
       int tiles[SG_MAX_TILES];
       for (int i = 0; i < n_tiles; ++i) tiles[i] = i;
       st = attention_canvas_tiles(*p, io->q, io->k, io->v, tiles, n_tiles, io->cache_out, s);
       if (st != SG_OK) return st;
     } else {
+      const int group = room < (size_t)n_tiles ? (int)room : n_tiles;
       const void* src[3] = {io->q, io->k, io->v};
-      for (int tr = 0; tr < p->n_tile_rows; ++tr)
-        for (int tc = 0; tc < p->n_tile_cols; ++tc) {
-          st = launch_slice(*p, src, 3, tr, tc, io->workspace, s);
+      const void* x[SG_MAX_TILES];
+      for (int t0 = 0; t0 < n_tiles; t0 += group) {
+        const int n = n_tiles - t0 < group ? n_tiles - t0 : group;
+        for (int i = 0; i < n; ++i) {
+          char* dst = (char*)io->workspace + (size_t)i * packed_bytes;
+          st = launch_slice(*p, src, 3, (t0 + i) / p->n_tile_cols, (t0 + i) % p->n_tile_cols, dst, s);
           if (st != SG_OK) return st;
-          const void* x = io->workspace;
-          st = attention_packed_tiles(*p, &x, 1, &io->cache_out[tr * p->n_tile_cols + tc], nullptr, s);
-          if (st != SG_OK) return st;
+          x[i] = dst;
         }
+        st = attention_packed_tiles(*p, x, n, io->cache_out + t0, nullptr, s);
+        if (st != SG_OK) return st;
+      }
     }
     return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);
   }

@@ -16,7 +16,7 @@ Sections (choose with --kernels, comma separated):
   refresh    sg_gain_refresh over 8 tiles, every second one recomputed
   std        sg_tile_std over 8 tile outputs
 Every section prints the bytes (or FLOP) the algorithm needs per launch, so a counter
-summary can be set beside it.  Inputs are synthetic N(0,1) values generated on the device.
+summary can be set beside it.  Inputs are seeded synthetic N(0,1) values generated on the device.
 """
 import argparse
 import os
@@ -37,7 +37,14 @@ def main():
     import numpy as np
     import torch
     import paper_2508_17756_amd as sg
-    from synthetic import CONFIGS
+    from synthetic import CONFIGS, randn_tensor
+
+    seed = [7000]
+
+    def rnd(shape, dtype="bf16"):
+        """seeded N(0,1) device tensor; every call takes the next seed"""
+        seed[0] += 1
+        return randn_tensor(shape, dtype, seed[0], device="cuda")
 
     sg.load_library()
     torch.cuda.set_device(0)
@@ -47,7 +54,7 @@ def main():
 
     if "copy" in todo:
         n = 1 << 30
-        a = torch.randn(n, dtype=torch.bfloat16, device="cuda")
+        a = rnd((n,))
         b = torch.empty_like(a)
         for _ in range(args.reps):
             torch.neg(a, out=b)          # one elementwise kernel: reads 2 GiB, writes 2 GiB
@@ -59,7 +66,7 @@ def main():
     if "attention" in todo:
         g = CONFIGS["tile720p_bf16"]
         p = sg.make_problem(g)
-        q, k, v = (torch.randn(g.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        q, k, v = (rnd(g.grid_shape) for _ in range(3))
         out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
         for _ in range(args.reps):
             sg.sg_tile_attention(p, q, k, v, 0, 0, out)
@@ -73,7 +80,7 @@ def main():
         from dataclasses import replace
         g = replace(CONFIGS["tile720p_bf16"], heads=48, head_dim=64)
         p = sg.make_problem(g)
-        q, k, v = (torch.randn(g.grid_shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+        q, k, v = (rnd(g.grid_shape) for _ in range(3))
         out = torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda")
         for _ in range(args.reps):
             sg.sg_tile_attention(p, q, k, v, 0, 0, out)
@@ -84,7 +91,7 @@ def main():
     if "blend" in todo:
         g = CONFIGS["canvas4k_bf16"]
         p = sg.make_problem(g)
-        tiles = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
+        tiles = [rnd(g.tile_shape) for _ in range(g.n_tiles)]
         canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
         for _ in range(args.reps):
             sg.sg_tile_blend(p, tiles, canvas)
@@ -96,8 +103,8 @@ def main():
     if "update" in todo:
         g = CONFIGS["canvas4k_bf16"]
         p = sg.make_problem(g)
-        tiles = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
-        latent = torch.randn(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+        tiles = [rnd(g.tile_shape) for _ in range(g.n_tiles)]
+        latent = rnd(g.grid_shape)
         for _ in range(args.reps):
             sg.sg_tile_blend_update(p, tiles, latent, 1.0, -0.02, latent)
         torch.cuda.synchronize()
@@ -109,11 +116,11 @@ def main():
     if "refresh" in todo or "std" in todo:
         g = CONFIGS["canvas4k_bf16"]
         n, E = 8, int(np.prod(g.tile_shape))
-        o_cur = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        o_cur = [rnd(g.tile_shape) for _ in range(n)]
         ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
         if "refresh" in todo:
-            o_prev = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            latent = [torch.randn(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            o_prev = [rnd(g.tile_shape) for _ in range(n)]
+            latent = [rnd(g.tile_shape) for _ in range(n)]
             delta = [torch.zeros(E, dtype=torch.float32, device="cuda") for _ in range(n)]
             state = sg.GainState(n)
             state.has_prev.fill_(1)
@@ -136,8 +143,8 @@ def main():
     if "gate" in todo:
         g = CONFIGS["canvas4k_bf16"]
         n, E = 4, int(np.prod(g.tile_shape))
-        cur = [torch.randn(3 * E, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-        old = [torch.randn(3 * E, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        cur = [rnd((3 * E,)) for _ in range(n)]
+        old = [rnd((3 * E,)) for _ in range(n)]
         has = torch.ones(n, dtype=torch.uint8, device="cuda")
         sc = torch.empty(n, dtype=torch.float32, device="cuda")
         rc = torch.empty(n, dtype=torch.uint8, device="cuda")

@@ -62,3 +62,38 @@ def test_cached_step_replays_from_a_graph():
             assert torch.equal(a, b)
         if k:
             assert graphed["rec"].cpu().tolist() == [int(e == 0.2) for e in eps[k]]
+
+
+@pytest.mark.parametrize("shift", [(0, 0), (3, 5)])
+def test_canvas_step_through_the_register_staged_kernel_replays_from_a_graph(shift):
+    """head_dim 64 read in place from a canvas takes the register-staged attention kernel (and, with a shift, its
+    wrapping loader): the canvas step captured once, replayed three times with eager work on the inputs in between,
+    must equal the eager step every time.  The first eager call does the kernel's one-time set-up outside of capture."""
+    g = _geom("graph64", 2, 14, 20, 8, 12, 6, 8, 2, 64, "bf16", 73)       # 2 x 2 overlapping tiles, N = 192
+    p = sg.make_problem(g, shift=shift)
+    qkv = [randn_tensor(g.grid_shape, "bf16", 950 + s).cuda() for s in range(3)]
+
+    def buffers():
+        return ([torch.zeros(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)],
+                torch.zeros(g.grid_shape, dtype=torch.bfloat16, device="cuda"))
+
+    (t_eager, c_eager), (t_graph, c_graph) = buffers(), buffers()
+    sg.sg_denoise_step_tiled(p, c_eager, t_eager, q=qkv[0], k=qkv[1], v=qkv[2])
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        sg.sg_denoise_step_tiled(p, c_graph, t_graph, q=qkv[0], k=qkv[1], v=qkv[2])
+    torch.cuda.synchronize()
+    for k in range(3):
+        if k:
+            for s in range(3):
+                perturb_(qkv[s], 0.3, 9500 + 10 * k + s)
+            sg.sg_denoise_step_tiled(p, c_eager, t_eager, q=qkv[0], k=qkv[1], v=qkv[2])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(c_graph, c_eager), k
+        for a, b in zip(t_graph, t_eager):
+            assert torch.equal(a, b), k
+        assert float(c_graph.float().abs().max()) > 0

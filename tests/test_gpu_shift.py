@@ -131,15 +131,17 @@ def test_shifted_step_bf16():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shift", [(0, 0), (3, 5)])
-def test_canvas_step_gathers_tiles_when_given_a_workspace(dtype, shift):
-    """Canvas mode with room for one packed tile in the workspace: same numbers as reading in place (bit for
-    bit, the arithmetic is the same) and, under a shifted partition, the oracle's shifted step."""
+@pytest.mark.parametrize("room", [1, 3, 4])
+def test_canvas_step_gathers_tiles_when_given_a_workspace(dtype, shift, room):
+    """Canvas mode with room for `room` packed tiles in the workspace (the 4 tiles go through in groups of 1, of 3 + 1,
+    or all at once): same numbers as reading in place (bit for bit, the arithmetic is the same) and, under a shifted
+    partition, the oracle's shifted step."""
     d = 64 if dtype == "f32" else 128
     g = _geom("cw", 2, 14, 20, 8, 12, 6, 8, 2, d, dtype, 41)              # 2 x 2 overlapping tiles
     td = torch_dtype(dtype)
     qkv = [randn_tensor(g.grid_shape, dtype, g.seed + 7 * s).cuda() for s in range(3)]
     E = int(np.prod(g.tile_shape))
-    ws = torch.empty(3 * E * (2 if dtype == "bf16" else 4) + 256, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(room * (3 * E * (2 if dtype == "bf16" else 4) + 256), dtype=torch.uint8, device="cuda")
     p = sg.make_problem(g, shift=shift)
     tiles = [torch.empty(g.tile_shape, dtype=td, device="cuda") for _ in range(g.n_tiles)]
     canvas = torch.empty(g.grid_shape, dtype=td, device="cuda")
