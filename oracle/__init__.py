@@ -16,6 +16,7 @@ from .tile_oracle import (  # noqa: F401
     blend,
     gate_score,
     cache_gate,
+    similarity,
     StepState,
     denoise_step_tiled,
     rel_l1,

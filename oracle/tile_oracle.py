@@ -165,6 +165,28 @@ def cache_gate(x_cur, x_cached, has_cache, threshold):
 
 
 # --------------------------------------------------------------------------
+# Similarity of a tensor across adjacent denoising steps (Equation 3): the
+# relative L1 distance with the earlier step's tensor in the denominator, and
+# the cosine similarity.  The paper profiles predicted noise and cache
+# residuals with this pair (Section 3, Section 5.1).
+# --------------------------------------------------------------------------
+def similarity(x_new, x_old):
+    """(L1_rel, CosSim) of Equation 3 for one pair of tensors.
+
+    L1_rel = ||x_new - x_old||_1 / ||x_old||_1 (+inf when the denominator is 0);
+    CosSim = <x_new, x_old> / (||x_new||_2 ||x_old||_2), taken as 0 when either
+    norm is 0 (the paper leaves the direction of a zero tensor open).
+    """
+    a = np.asarray(x_new, dtype=np.float64).ravel()
+    b = np.asarray(x_old, dtype=np.float64).ravel()
+    assert a.shape == b.shape
+    l1 = gate_score(a, b)
+    na, nb = float(np.sqrt((a * a).sum())), float(np.sqrt((b * b).sum()))
+    cos = 0.0 if na == 0.0 or nb == 0.0 else float((a * b).sum() / (na * nb))
+    return l1, cos
+
+
+# --------------------------------------------------------------------------
 # One tiled denoising step with the tile-wise cache store
 # (Algorithm 1 stage-2 loop body; Section 5.1 pipeline: gate -> recompute or
 # reuse -> Tile Fuser)

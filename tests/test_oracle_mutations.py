@@ -8,8 +8,8 @@ import sys
 
 import pytest
 
-A, B, G, N, R, S = ("test_oracle_attention.py", "test_oracle_blend.py", "test_oracle_gate.py",
-                    "test_oracle_gain.py", "test_oracle_region.py", "test_oracle_shift.py")
+A, B, G, N, R, S, M = ("test_oracle_attention.py", "test_oracle_blend.py", "test_oracle_gate.py",
+                       "test_oracle_gain.py", "test_oracle_region.py", "test_oracle_shift.py", "test_oracle_similarity.py")
 
 MUTATIONS = [
     # name, pin file, text in oracle/tile_oracle.py, replacement
@@ -32,6 +32,11 @@ MUTATIONS = [
      "recompute.append(not (bool(hc) and s <= float(threshold)))"),
     ("gate_nan_score_reuses", G, "recompute.append(not (bool(hc) and s < float(threshold)))",
      "recompute.append(bool((not hc) or s >= float(threshold)))"),
+    ("cosine_normalised_by_l1_norms", M, "na, nb = float(np.sqrt((a * a).sum())), float(np.sqrt((b * b).sum()))",
+     "na, nb = float(np.abs(a).sum()), float(np.abs(b).sum())"),
+    ("cosine_of_magnitudes", M, "float((a * b).sum() / (na * nb))", "float(np.abs(a * b).sum() / (na * nb))"),
+    ("cosine_divides_by_one_norm_squared", M, "float((a * b).sum() / (na * nb))", "float((a * b).sum() / (nb * nb))"),
+    ("similarity_l1_denominator_is_new", M, "    l1 = gate_score(a, b)\n", "    l1 = gate_score(b, a)\n"),
     ("gain_tie_reuses", N, "recompute[i] = not (scores[i] < float(thresholds[i]))",
      "recompute[i] = not (scores[i] <= float(thresholds[i]))"),
     ("path_length_not_accumulated", N, "state.path_len[i] += d[i]", "state.path_len[i] = d[i]"),
@@ -65,7 +70,7 @@ def sandbox(repo_root, tmp_path_factory):
     shutil.copytree(os.path.join(repo_root, "synthetic"), box / "synthetic", ignore=ignore)
     os.makedirs(box / "tests")
     shutil.copytree(os.path.join(repo_root, "tests", "golden"), box / "tests" / "golden")
-    for f in (A, B, G, N, R, S, "conftest.py"):
+    for f in (A, B, G, N, R, S, M, "conftest.py"):
         shutil.copy(os.path.join(repo_root, "tests", f), box / "tests" / f)
     return box
 
@@ -76,7 +81,7 @@ def _run_pins(box, test_file):
 
 
 def test_the_unmutated_copy_passes(sandbox):
-    for f in (B, G, N, R, S):       # the attention pins run in the main suite; here they would only pay torch's import again
+    for f in (B, G, N, R, S, M):    # the attention pins run in the main suite; here they would only pay torch's import again
         r = _run_pins(sandbox, f)
         assert r.returncode == 0, r.stdout[-2000:]
 
