@@ -508,6 +508,13 @@ def policy_extras(torch, sg, args, kept):
     ms_s = time_calls(torch, lambda: sg.sg_tile_std(o_cur, tstd, ws), 10)
     res["tile_std_4k"] = {"ms": round(ms_s, 4), "GB/s": round(2.0 * E * n5 / ms_s * 1e-6, 1),
                           "frac_hbm_peak": round(2.0 * E * n5 / ms_s * 1e-6 / PEAK_HBM_GBS, 4)}
+    # Equation 3's similarity pair (relative L1 distance, cosine) of the 20 outputs against 20 others: reads both once
+    o_old = [randn_tensor(g5.tile_shape, "bf16", g5.seed + 600 + i, device="cuda") for i in range(n5)]
+    cosv = torch.empty(n5, dtype=torch.float32, device="cuda")
+    ms_c = time_calls(torch, lambda: sg.sg_tile_similarity(o_cur, o_old, tstd, cosv, ws), 10)
+    res["similarity_4k"] = {"ms": round(ms_c, 4), "GB/s": round(4.0 * E * n5 / ms_c * 1e-6, 1),
+                            "frac_hbm_peak": round(4.0 * E * n5 / ms_c * 1e-6 / PEAK_HBM_GBS, 4)}
+    del o_old
     res["gain_refresh_4k"] = {"ms": round(ms_r, 4), "GB/s": round(nb / ms_r * 1e-6, 1),
                               "frac_hbm_peak": round(nb / ms_r * 1e-6 / PEAK_HBM_GBS, 4), "recomputed_tiles": int(half.sum())}
     return res

@@ -186,6 +186,18 @@ int sg_cache_gate_static(const void* const* x_cur, const void* const* x_cached, 
                          int32_t n_tiles, int64_t elems_per_tile, int32_t dtype, float threshold,
                          float* scores, uint8_t* recompute, void* stream);
 
+/*
+ * Similarity of a tile tensor across adjacent denoising steps (Equation 3, both measures), per tile i:
+ *     l1_rel[i]  = sum|x_new[i] - x_old[i]| / sum|x_old[i]|      (+inf if the sum is 0; sg_cache_gate's score)
+ *     cos_sim[i] = <x_new[i], x_old[i]> / (||x_new[i]||_2 ||x_old[i]||_2)   (0 if either norm is 0)
+ * the pair the paper profiles predicted noise and cache residuals with (Section 3; Section 5.1).  One read of
+ * both tensors; sums in fp32 per thread, fp64 across threads in a fixed order.
+ *   x_new, x_old   host arrays of n_tiles device pointers, elems_per_tile elements of `dtype`, 16-byte aligned
+ *   l1_rel, cos_sim  device, n_tiles floats each (out);  workspace: as sg_cache_gate
+ */
+int sg_tile_similarity(const void* const* x_new, const void* const* x_old, int32_t n_tiles, int64_t elems_per_tile,
+                       int32_t dtype, float* l1_rel, float* cos_sim, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Buffers of one tiled step.  All arrays of pointers are host arrays of device pointers. */
 typedef struct sg_step_io {
   /* Canvas mode (gate off): q, k, v are canvas tensors and every tile is recomputed.        */

@@ -133,6 +133,8 @@ def load_library():
                                           ctypes.POINTER(sg_region_control), ctypes.POINTER(sg_scheduler_update), vp]
     lib.sg_tile_std.restype = ctypes.c_int
     lib.sg_tile_std.argtypes = [pp, i32, i64, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.sg_tile_similarity.restype = ctypes.c_int
+    lib.sg_tile_similarity.argtypes = [pp, pp, i32, i64, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.sg_region_thresholds.restype = ctypes.c_int
     lib.sg_region_thresholds.argtypes = [vp, vp, vp, i32, f32, f32, i32, i32, vp, vp, vp]
     _LIB = lib
@@ -385,6 +387,17 @@ def sg_tile_std(x, tile_std, workspace, elems_per_tile=None):
                                     _stream())
     _check(rc, "sg_tile_std")
     return tile_std
+
+
+def sg_tile_similarity(x_new, x_old, l1_rel, cos_sim, workspace, elems_per_tile=None):
+    """Equation 3 per tile: relative L1 distance (x_old in the denominator) and cosine similarity."""
+    n = len(x_new)
+    elems = int(elems_per_tile if elems_per_tile is not None else (x_new[0].numel() if n else 0))
+    dt = _dtype_code(x_new[0]) if n else SG_BF16
+    rc = load_library().sg_tile_similarity(_ptr_array(x_new), _ptr_array(x_old), n, elems, dt, _ptr(l1_rel), _ptr(cos_sim),
+                                           _ptr(workspace), _nbytes(workspace), _stream())
+    _check(rc, "sg_tile_similarity")
+    return l1_rel, cos_sim
 
 
 def sg_region_thresholds(tile_std, track_mean, track_count, tau_base, alpha, mode, adjust, thresholds, sigma=None):

@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsupergen_tile.so")
 PROBE = os.path.join(PKG, "peak_probe.bin")
 SOURCES = ["sg_api.hip", "attention_bf16.hip", "attention_bf16_generic.hip", "attention_f32.hip", "blend.hip",
-           "gate.hip", "gate_static.hip", "region.hip"]
+           "gate.hip", "gate_static.hip", "region.hip", "similarity.hip"]
 # per-file extras: the streaming attention kernel takes row maxima with three-operand max instructions,
 # which the compiler only forms when it need not canonicalise NaNs
 EXTRA = {"attention_bf16.hip": ["-fno-honor-nans"]}

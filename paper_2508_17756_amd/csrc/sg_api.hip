@@ -420,6 +420,18 @@ int sg_tile_std(const void* const* x, int32_t n_tiles, int64_t elems_per_tile, i
   return launch_tile_std(x, n_tiles, elems_per_tile, dtype, tile_std, workspace, (hipStream_t)stream);
 }
 
+int sg_tile_similarity(const void* const* x_new, const void* const* x_old, int32_t n_tiles, int64_t elems_per_tile,
+                       int32_t dtype, float* l1_rel, float* cos_sim, void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_tiles < 0 || elems_per_tile < 0) return SG_ERR_INVALID_ARG;
+  if (dtype != SG_F32 && dtype != SG_BF16) return SG_ERR_INVALID_ARG;
+  if (n_tiles == 0) return SG_OK;
+  if (!l1_rel || !cos_sim || check_ptr_array(x_new, n_tiles) != SG_OK || check_ptr_array(x_old, n_tiles) != SG_OK)
+    return SG_ERR_INVALID_ARG;
+  if (!workspace || (((uintptr_t)workspace) & 255u) || workspace_bytes < gate_workspace_bytes(n_tiles))
+    return SG_ERR_WORKSPACE;
+  return launch_similarity(x_new, x_old, n_tiles, elems_per_tile, dtype, l1_rel, cos_sim, workspace, (hipStream_t)stream);
+}
+
 int sg_region_thresholds(const float* tile_std, double* track_mean, int32_t* track_count, int32_t n_tiles,
                          float tau_base, float alpha, int32_t mode, int32_t adjust, float* sigma, float* thresholds,
                          void* stream) {

@@ -57,6 +57,8 @@ int launch_gain_refresh(void* const* out_cur, const void* const* out_prev, const
                         float* const* delta, const uint8_t* recompute, const float* step_change,
                         const sg_gain_state& gs, int n_tiles, int64_t elems, int dtype, void* ws, hipStream_t s);
 int launch_tile_std(const void* const* x, int n_tiles, int64_t elems, int dtype, float* tile_std, void* ws, hipStream_t s);
+int launch_similarity(const void* const* x_new, const void* const* x_old, int n_tiles, int64_t elems, int dtype,
+                      float* l1_rel, float* cos_sim, void* ws, hipStream_t s);
 int launch_region_thresholds(const float* tile_std, double* track_mean, int32_t* track_count, int n_tiles,
                              float tau_base, float alpha, int mode, int adjust, float* sigma, float* thresholds,
                              hipStream_t s);

@@ -82,6 +82,9 @@ def test_null_and_workspace_checks_need_no_gpu():
     assert lib.sg_gain_refresh(arr, arr, arr, None, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_gain_refresh(arr, arr, arr, arr, 256, 256, ctypes.byref(st), 2, 64, sg.SG_BF16, 256, 16, None) == sg.SG_ERR_WORKSPACE
     assert lib.sg_denoise_step_gain(ctypes.byref(p), None, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_similarity(arr, arr, 2, 64, sg.SG_BF16, 256, None, 256, 1 << 20, None) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_tile_similarity(arr, arr, 2, 64, sg.SG_BF16, 256, 256, 256, 16, None) == sg.SG_ERR_WORKSPACE
+    assert lib.sg_tile_similarity(None, None, 0, 64, sg.SG_BF16, None, None, None, 0, None) == sg.SG_OK
     # shifted partitions
     ps = sg.make_problem(CONFIGS["tiny_f32"], shift=(3, 5))
     assert sg.sg_problem_validate(ps) == sg.SG_OK

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_2508_17756_amd as sg
-from synthetic import randn_tensor, torch_dtype
+from synthetic import randn_tensor, torch_dtype, perturb_
 from gpu_util import to_f64
 
 pytestmark = pytest.mark.gpu
@@ -99,3 +99,50 @@ def test_std_tracker_drives_the_gain_gate_thresholds():
     torch.cuda.synchronize()
     assert all(abs(v - 0.0625) < 1e-3 for v in scores.cpu().tolist())             # thresholds 0.04, 0.07, 0.05
     assert rec.cpu().tolist() == [1, 0, 1]
+
+
+# ------------------------------------------------------------------ similarity pair of Equation 3
+def _similarity(x_new, x_old):
+    n = len(x_new)
+    l1 = torch.full((max(n, 1),), -5.0, dtype=torch.float32, device="cuda")
+    cs = torch.full((max(n, 1),), -5.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(sg.sg_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    sg.sg_tile_similarity(x_new, x_old, l1, cs, ws)
+    torch.cuda.synchronize()
+    return l1.cpu().numpy()[:n], cs.cpu().numpy()[:n]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("elems", [8, 1000, 4099, 3 * 2 * 3 * 10 * 10 * 64, (1 << 20) + 3])
+def test_similarity_against_the_oracle(dtype, elems):
+    """Relative L1 distance and cosine similarity (Equation 3) of five tile pairs: identical, barely moved, moved,
+    opposite, unrelated; element counts that are ragged against the 16-byte vectors and against the workgroups."""
+    n = 5
+    old = [randn_tensor((elems,), dtype, 2100 + i).cuda() for i in range(n)]
+    new = [old[0].clone(), perturb_(old[1].clone(), 0.01, 2201), perturb_(old[2].clone(), 0.5, 2202), -old[3],
+           randn_tensor((elems,), dtype, 2204).cuda()]
+    l1, cs = _similarity(new, old)
+    for i in range(n):
+        ref_l1, ref_cs = oracle.similarity(to_f64(new[i]), to_f64(old[i]))
+        assert abs(l1[i] - ref_l1) <= 2e-6 * max(1.0, ref_l1), (i, l1[i], ref_l1)
+        assert abs(cs[i] - ref_cs) <= 3e-6, (i, cs[i], ref_cs)
+    assert l1[0] == 0.0 and abs(cs[0] - 1.0) <= 3e-6 and abs(cs[3] + 1.0) <= 3e-6 and abs(l1[3] - 2.0) <= 4e-6
+
+
+def test_similarity_zero_tensors_many_tiles_and_arguments():
+    x = randn_tensor((4096,), "bf16", 2300).cuda()
+    z = torch.zeros_like(x)
+    l1, cs = _similarity([x, z, z], [z, x, z])
+    assert np.isinf(l1[0]) and cs[0] == 0.0 and l1[1] == 1.0 and cs[1] == 0.0 and np.isinf(l1[2]) and cs[2] == 0.0
+    n = 70                                                           # more than one launch's table of pointers
+    old = [randn_tensor((2048,), "bf16", 2400 + i).cuda() for i in range(n)]
+    new = [perturb_(t.clone(), 0.05 * (1 + i % 4), 2500 + i) for i, t in enumerate(old)]
+    l1, cs = _similarity(new, old)
+    for i in (0, 1, 63, 64, 69):
+        ref_l1, ref_cs = oracle.similarity(to_f64(new[i]), to_f64(old[i]))
+        assert abs(l1[i] - ref_l1) <= 2e-6 * max(1.0, ref_l1) and abs(cs[i] - ref_cs) <= 3e-6, i
+    _similarity([], [])
+    with pytest.raises(sg.SgError) as e:
+        sg.sg_tile_similarity([x], [x], torch.empty(1, device="cuda"), torch.empty(1, device="cuda"),
+                              torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == sg.SG_ERR_WORKSPACE
