@@ -233,7 +233,8 @@ typedef struct sg_step_io {
  *     tiles keep their cache entries untouched (drift stays measured from the last recomputed
  *     step); grid_out = Fuse of all cache_out.
  * The decisions stay on the device and nothing is read back: one attention launch covers all tiles
- * and numbers only the work of the tiles to recompute.
+ * and numbers only the work of the tiles to recompute; for bf16 problems the same launch also carries
+ * the cache refresh, on the compute units its last, partial round of workgroups leaves idle.
  */
 int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* stream);
 

@@ -147,7 +147,8 @@ enum { kPerLane = 0, kLinear = 1, kScalarWalk = 2, kWrapped = 3 };   // how the 
 template <int D, int MODE>
 __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 vw, const float c_log2, const int heads,
                                                                   const int n_qblocks, const int n_tiles, const AttnTable tab,
-                                                                  const uint8_t* __restrict__ run_flags) {
+                                                                  const uint8_t* __restrict__ run_flags, const int first_copy_block,
+                                                                  const int64_t copy_vecs, uint8_t* __restrict__ has_cache) {
   static_assert(D == 128 || D == 64, "head_dim 64 or 128");
   static_assert(D == 128 || MODE == kLinear, "head_dim 64 streams packed tiles only");
   // LDS rows ("slots") are always 256 bytes.  With head_dim 128 a slot is one key and a stage 64 keys; with
@@ -170,7 +171,31 @@ __global__ __launch_bounds__(kThreads) void attention_bf16_kernel(const View16 v
   const int per_xcd = (total + kXcd - 1) / kXcd;
   const int xcd = blockIdx.x % kXcd, slot = blockIdx.x / kXcd;
   const int logical = xcd * per_xcd + slot;
-  if (slot >= per_xcd || logical >= total) return;
+  if (slot >= per_xcd || logical >= total) {
+    // The workgroups behind the attention grid carry the step's cache refresh (cache_x <- x for the tiles that run):
+    // they are dispatched last, onto the compute units the attention's final, partial round leaves idle, and
+    // stream through HBM, which the attention hardly uses.  Chunks of one vector per thread are dealt round-robin,
+    // so the copy walks both buffers as one contiguous window.
+    if ((int)blockIdx.x < first_copy_block) return;
+    const int c = blockIdx.x - first_copy_block, n_copy = gridDim.x - first_copy_block;
+    for (uint32_t m = active; m; m &= m - 1) {
+      const int t = __builtin_ctz(m);
+      const u32x4* __restrict__ src = (const u32x4*)tab.q[t];
+      u32x4* __restrict__ dst = (u32x4*)tab.refresh[t];
+      int64_t i = (int64_t)c * kThreads + threadIdx.x;
+      const int64_t step = (int64_t)n_copy * kThreads;
+      for (; i + 7 * step < copy_vecs; i += 8 * step) {   // eight 16-byte loads in flight per thread
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * step);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(v[u], dst + i + u * step);
+      }
+      for (; i < copy_vecs; i += step) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+      if (c == 0 && threadIdx.x == 0) has_cache[t] = 1;
+    }
+    return;
+  }
   const int nth = logical / per_tile, in_tile = logical - nth * per_tile;
   const int tile = __builtin_amdgcn_readfirstlane(attn_nth_tile(active, nth));
   const int head = in_tile / n_qblocks, qblk = in_tile - head * n_qblocks;
@@ -666,8 +691,13 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
   // the kernels need more dynamic LDS than the default limit; the attribute is set once per device and kernel
   constexpr int kMaxDevices = 64;
   static std::atomic<bool> attr_set[kMaxDevices][5];   // zero-initialised; set twice by racing threads is harmless
-  int dev = 0;
+  int dev = 0, n_cu = 0;
   SG_HIP_TRY(hipGetDevice(&dev));
+  SG_HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  if (n_cu < 4) n_cu = 4;
+  // the cache refresh rides on this launch for packed tiles (their inputs are one contiguous run each)
+  const bool fuse_refresh = b.refresh_dst && b.has_cache && b.refresh_bytes > 0 && (b.refresh_bytes & 15) == 0 && linear;
+  bool tab_refresh_ok = false;
   for (int t0 = 0; t0 < b.n_tiles; t0 += kAttnTilesPerLaunch) {
     const int n = (b.n_tiles - t0 < kAttnTilesPerLaunch) ? b.n_tiles - t0 : kAttnTilesPerLaunch;
     AttnTable tab;
@@ -681,15 +711,27 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
       tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
     }
     const int64_t total = (int64_t)n * heads * n_qblocks;   // the grid covers every tile; skipped tiles' share exits at once
-    if (total > (1ll << 31) - 2 * kXcd) return SG_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)(((total + kXcd - 1) / kXcd) * kXcd));
+    const int64_t attn_blocks = ((total + kXcd - 1) / kXcd) * kXcd;
+    // fused cache refresh: as many copy workgroups as the attention's last round leaves compute units idle (at least
+    // a quarter of the device), appended to the grid
+    int64_t copy_blocks = 0;
+    if (fuse_refresh) {
+      copy_blocks = n_cu - attn_blocks % n_cu;
+      if (copy_blocks < n_cu / 4) copy_blocks += n_cu;
+      tab_refresh_ok = true;
+    }
+    if (attn_blocks + copy_blocks > (1ll << 31) - 1) return SG_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(attn_blocks + copy_blocks));
     const uint8_t* flags = b.run_flags ? b.run_flags + t0 : nullptr;
+    for (int i = 0; i < kAttnTilesPerLaunch; ++i) tab.refresh[i] = (fuse_refresh && i < n) ? b.refresh_dst[t0 + i] : nullptr;
     auto launch = [&](auto kern, int slot) -> int {
       if (dev < 0 || dev >= kMaxDevices || !attr_set[dev][slot].load(std::memory_order_acquire)) {
         SG_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
         if (dev >= 0 && dev < kMaxDevices) attr_set[dev][slot].store(true, std::memory_order_release);
       }
-      kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, n, tab, flags);
+      kern<<<grid, kThreads, kLdsBytes, s>>>(vw, c_log2, heads, n_qblocks, n, tab, flags, (int)attn_blocks,
+                                             fuse_refresh ? b.refresh_bytes / 16 : 0,
+                                             fuse_refresh ? b.has_cache + t0 : nullptr);
       return SG_OK;
     };
     int st = SG_OK;
@@ -701,6 +743,7 @@ int launch_attention_bf16(const TileView& tv, int heads, int head_dim, float sca
     if (st != SG_OK) return st;
     SG_HIP_TRY(hipGetLastError());
   }
+  if (b.refreshed) *b.refreshed = tab_refresh_ok;
   return SG_OK;
 }
 

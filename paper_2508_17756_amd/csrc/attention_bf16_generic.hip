@@ -310,6 +310,7 @@ int launch_attention_bf16_generic(const TileView& tv, int heads, int head_dim, f
       tab.out[i] = in ? b.out[t0 + i] : nullptr;
       tab.y0[i] = (in && b.y0) ? b.y0[t0 + i] : 0;
       tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
+      tab.refresh[i] = nullptr;   // the cache refresh is not carried by this kernel
     }
     const int64_t total = (int64_t)n * heads * n_qblocks;
     if (total > (1ll << 31) - 2 * kXcd) return SG_ERR_UNSUPPORTED;

@@ -26,6 +26,7 @@ struct AttnTable {
   const void* v[kAttnTilesPerLaunch];
   void* out[kAttnTilesPerLaunch];
   int32_t y0[kAttnTilesPerLaunch], x0[kAttnTilesPerLaunch];   // wrapped windows only
+  void* refresh[kAttnTilesPerLaunch];   // cache refresh fused into the launch (packed tiles): copy of the tile's input, or unused
 };
 
 // Tiles whose run flag is 0 (the cache gate reuses them) are skipped on the device: the workgroups number

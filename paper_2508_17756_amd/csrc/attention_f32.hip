@@ -188,6 +188,7 @@ int launch_attention_f32(const TileView& tv, int heads, int head_dim, float scal
       tab.out[i] = in ? b.out[t0 + i] : nullptr;
       tab.y0[i] = (in && b.y0) ? b.y0[t0 + i] : 0;
       tab.x0[i] = (in && b.x0) ? b.x0[t0 + i] : 0;
+      tab.refresh[i] = nullptr;   // the cache refresh is not carried by this kernel
     }
     const dim3 grid((tv.N + kQ - 1) / kQ, heads, n);
     const uint8_t* flags = b.run_flags ? b.run_flags + t0 : nullptr;

@@ -90,7 +90,7 @@ static int attention_canvas_tiles(const sg_problem& p, const void* q, const void
       ++m;
     }
     if (!m) continue;
-    const AttnBatch b = {m, qp, kp, vp, op, pass ? y0 : nullptr, pass ? x0 : nullptr, nullptr};
+    const AttnBatch b = {m, qp, kp, vp, op, pass ? y0 : nullptr, pass ? x0 : nullptr, nullptr, nullptr, nullptr, 0, nullptr};
     const int st = attention_launch(p, make_view(p, pass == 1), b, s);
     if (st != SG_OK) return st;
   }
@@ -98,9 +98,12 @@ static int attention_canvas_tiles(const sg_problem& p, const void* q, const void
 }
 
 // Attention of packed tile inputs x[i] = [3][heads][T][tile_h][tile_w][d] (Q, K, V) in one launch; tiles whose
-// run flag (device) is 0 are skipped on the device.
+// run flag (device) is 0 are skipped on the device.  With cache_x / has_cache the step's cache refresh (cache_x[i] <-
+// x[i], has_cache[i] <- 1 for the tiles that run) rides on the same launch where the kernel can carry it, and is a
+// launch of its own otherwise.
 static int attention_packed_tiles(const sg_problem& p, const void* const* x, int n, void* const* out,
-                                  const uint8_t* run_flags, hipStream_t s) {
+                                  const uint8_t* run_flags, hipStream_t s, void* const* cache_x = nullptr,
+                                  uint8_t* has_cache = nullptr) {
   const sg_problem tp = packed_tile_problem(p);
   const size_t part = (size_t)p.heads * p.T * p.tile_h * p.tile_w * p.head_dim * (p.dtype == SG_BF16 ? 2 : 4);
   const void* qp[SG_MAX_TILES]; const void* kp[SG_MAX_TILES]; const void* vp[SG_MAX_TILES];
@@ -109,8 +112,12 @@ static int attention_packed_tiles(const sg_problem& p, const void* const* x, int
     kp[i] = (const char*)x[i] + part;
     vp[i] = (const char*)x[i] + 2 * part;
   }
-  const AttnBatch b = {n, qp, kp, vp, out, nullptr, nullptr, run_flags};
-  return attention_launch(tp, make_view(tp, false), b, s);
+  bool refreshed = false;
+  const AttnBatch b = {n, qp, kp, vp, out, nullptr, nullptr, run_flags, cache_x, has_cache,
+                       cache_x ? (int64_t)(3 * part) : 0, &refreshed};
+  const int st = attention_launch(tp, make_view(tp, false), b, s);
+  if (st != SG_OK || !cache_x || refreshed) return st;
+  return launch_cache_refresh(x, cache_x, run_flags, has_cache, n, (int64_t)(3 * part), s);
 }
 
 }  // namespace sg
@@ -265,10 +272,7 @@ int sg_denoise_step_tiled(const sg_problem* p, const sg_step_io* io, void* strea
   st = launch_gate(io->tile_x, (const void* const*)io->cache_x, io->has_cache, n_tiles, 3 * tile_elems, p->dtype,
                    io->threshold, io->scores, io->recompute, io->workspace, s);
   if (st != SG_OK) return st;
-  st = attention_packed_tiles(*p, io->tile_x, n_tiles, io->cache_out, io->recompute, s);
-  if (st != SG_OK) return st;
-  st = launch_cache_refresh(io->tile_x, io->cache_x, io->recompute, io->has_cache, n_tiles,
-                            3 * tile_elems * (int64_t)esz, s);
+  st = attention_packed_tiles(*p, io->tile_x, n_tiles, io->cache_out, io->recompute, s, io->cache_x, io->has_cache);
   if (st != SG_OK) return st;
   return launch_blend(*p, (const void* const*)io->cache_out, io->grid_out, nullptr, 0.f, 0.f, s);
 }

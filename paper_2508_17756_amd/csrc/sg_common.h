@@ -36,6 +36,13 @@ struct AttnBatch {
   const int32_t* y0;         // host arrays, wrapped windows only (else nullptr)
   const int32_t* x0;
   const uint8_t* run_flags;  // device, n_tiles bytes: tiles with a 0 are skipped; nullptr = all tiles run
+  // Cache refresh of the tiled step, carried out by the same launch where the kernel supports it (*refreshed is
+  // then set): for every tile that runs, refresh_dst[i] <- the refresh_bytes at q[i] (a packed tile input: Q, K, V
+  // one after the other) and has_cache[i] <- 1.  All nullptr / 0 when no refresh is asked for.
+  void* const* refresh_dst;  // host array of n_tiles device pointers
+  uint8_t* has_cache;        // device, n_tiles bytes
+  int64_t refresh_bytes;     // a multiple of 16
+  bool* refreshed;           // host, out
 };
 
 // Launchers (each validates nothing: the API layer has already done so).
