@@ -528,7 +528,7 @@ def main():
     ap.add_argument("--workload", default="tile720p_bf16")
     ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
     ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
-    ap.add_argument("--full", action="store_true", help="also time the 4K step with gathered tiles and the 720p tile at 48 heads x 64")
+    ap.add_argument("--full", action="store_true", help="also time the 720p tile at 48 heads x 64")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="query rows per head of the CPU baseline sample")
     ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the CPU baseline sample")
     args = ap.parse_args()

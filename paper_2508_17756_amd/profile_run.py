@@ -15,6 +15,7 @@ Sections (choose with --kernels, comma separated):
   update     sg_tile_blend_update of the 4K canvas (blend + scheduler update in place)
   refresh    sg_gain_refresh over 8 tiles, every second one recomputed
   std        sg_tile_std over 8 tile outputs
+  similarity sg_tile_similarity over 8 pairs of tile outputs
 Every section prints the bytes (or FLOP) the algorithm needs per launch, so a counter
 summary can be set beside it.  Inputs are seeded synthetic N(0,1) values generated on the device.
 """
@@ -29,7 +30,7 @@ if ROOT not in sys.path:
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--kernels", default="copy,attention,blend,gate,update,refresh,std")
+    ap.add_argument("--kernels", default="copy,attention,blend,gate,update,refresh,std,similarity")
     ap.add_argument("--reps", type=int, default=3)
     args = ap.parse_args()
     todo = args.kernels.split(",")
@@ -113,7 +114,7 @@ def main():
                2 * int(np.prod(g.grid_shape))))
         del tiles, latent
 
-    if "refresh" in todo or "std" in todo:
+    if "refresh" in todo or "std" in todo or "similarity" in todo:
         g = CONFIGS["canvas4k_bf16"]
         n, E = 8, int(np.prod(g.tile_shape))
         o_cur = [rnd(g.tile_shape) for _ in range(n)]
@@ -138,6 +139,15 @@ def main():
                 sg.sg_tile_std(o_cur, out, ws)
             torch.cuda.synchronize()
             say("std: %d launches over %d tiles, per launch %d bytes read" % (args.reps, n, 2 * E * n))
+        if "similarity" in todo:
+            o_old = [rnd(g.tile_shape) for _ in range(n)]
+            l1 = torch.empty(n, dtype=torch.float32, device="cuda")
+            cs = torch.empty(n, dtype=torch.float32, device="cuda")
+            for _ in range(args.reps):
+                sg.sg_tile_similarity(o_cur, o_old, l1, cs, ws)
+            torch.cuda.synchronize()
+            say("similarity: %d launches over %d tiles, per launch %d bytes read" % (args.reps, n, 2 * 2 * E * n))
+            del o_old
         del o_cur
 
     if "gate" in todo:
