@@ -524,7 +524,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=15)
     ap.add_argument("--workload", default="tile720p_bf16")
     ap.add_argument("--heads", type=int, default=0, help="override head count (probing only; invalidates the number)")
     ap.add_argument("--no-extras", action="store_true", help="skip the blend/gate kernel figures and the CPU baseline")
