@@ -9,6 +9,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsupergen_tile.so")
 PROBE = os.path.join(PKG, "peak_probe.bin")
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_client", "gpu_client.c")
+C_CLIENT = os.path.join(ROOT, "tests", "c_client", "gpu_client.bin")
 SOURCES = ["sg_api.hip", "attention_bf16.hip", "attention_bf16_generic.hip", "attention_f32.hip", "blend.hip",
            "gate.hip", "gate_static.hip", "region.hip", "similarity.hip"]
 # per-file extras: the streaming attention kernel takes row maxima with three-operand max instructions,
@@ -46,6 +48,12 @@ def build(verbose=False):
     # stand-alone probe of the device's achievable MFMA and HBM rates (bench.py sets it beside the vendor peaks)
     _run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           os.path.join(CSRC, "peak_probe.hip"), "-o", PROBE])
+    # the plain C caller of the device-side entry points that the GPU tests start as a child process (host compiler only)
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    _run([os.environ.get("CC", "gcc"), "-std=c99", "-Wall", "-Wextra", "-O1", "-D__HIP_PLATFORM_AMD__",
+          "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"), C_CLIENT_SRC, "-o", C_CLIENT,
+          "-L", PKG, "-lsupergen_tile", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+          "-Wl,-rpath,$ORIGIN/../../paper_2508_17756_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")])
     return LIB
 
 
