@@ -1,6 +1,8 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
 the header declares, validates problems and rejects bad arguments before any launch."""
 import ctypes
+import subprocess
+import sys
 import re
 
 import pytest
@@ -114,7 +116,6 @@ def test_plain_c_client_compiles_links_and_agrees_on_layout(repo_root, tmp_path)
     library and calls the host-only entry points; the sizes the C compiler derives are the binding's."""
     import os
     import shutil
-    import subprocess
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no C compiler")
@@ -140,3 +141,10 @@ def test_plain_c_client_compiles_links_and_agrees_on_layout(repo_root, tmp_path)
     assert int(kv["workspace_status"]) == sg.SG_OK and int(kv["workspace_bytes"]) == sg.sg_workspace_bytes(20)
     assert int(kv["null_attention"]) == int(kv["null_blend"]) == int(kv["null_step"]) == sg.SG_ERR_INVALID_ARG
     assert kv["status_string"] == "invalid argument"
+
+
+def test_bench_refuses_more_than_one_gpu(repo_root):
+    """One GPU only: asking the benchmark for more ends with a message, before anything touches a device."""
+    run = subprocess.run([sys.executable, f"{repo_root}/bench.py", "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert run.returncode != 0
+    assert "one GPU" in (run.stdout + run.stderr)
