@@ -29,6 +29,7 @@ from .tile_oracle import (  # noqa: F401
     tile_std,
     StdTracker,
     region_thresholds,
+    shift_schedule,
     slice_tile_shifted,
     blend_shifted,
     fuse_and_denoise,

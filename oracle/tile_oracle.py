@@ -429,6 +429,26 @@ def region_thresholds(sigma, tau_base, alpha, mode):
 # sits at canvas position ((r0 + i + dy) mod H, (c0 + j + dx) mod W).  That is the
 # unshifted partition applied to the canvas rolled by (-dy, -dx).
 # --------------------------------------------------------------------------
+def shift_schedule(step, tile_h, tile_w, loop_step=16, frequency=1):
+    """Offset (dy, dx) of the partition at denoising step `step` = 0, 1, ... (Algorithm 1
+    "ShiftThisStep" / "Shift"; Section 8 "Workloads": loop step 16, i.e. a shift stride of
+    1/16 of the tile size, shifting every step; appendix: loop step = 1 / shift stride, and a
+    frequency x shifts every x steps).
+
+    The partition moves after every `frequency`-th step, along both directions at once, by
+    1 / loop_step of the tile size; after loop_step moves it has travelled one whole tile,
+    which for equal non-overlapping tiles on a wrapping canvas is the partition it started
+    from, so the count of moves is taken modulo loop_step.  Where the tile size is not a
+    multiple of loop_step the s-th position is floor(s * tile / loop_step): the stride stays
+    1 / loop_step of a tile on average and the loop still closes.
+    """
+    step, loop_step, frequency = int(step), int(loop_step), int(frequency)
+    if step < 0 or loop_step < 1 or frequency < 1:
+        raise ValueError("step >= 0, loop_step >= 1, frequency >= 1")
+    moves = (step // frequency) % loop_step
+    return (moves * int(tile_h)) // loop_step, (moves * int(tile_w)) // loop_step
+
+
 def slice_tile_shifted(grid, g, tile_row, tile_col, shift_h, shift_w):
     """SliceTile under a shifted partition: the unshifted window of the rolled canvas."""
     rolled = np.roll(np.asarray(grid), shift=(-int(shift_h), -int(shift_w)), axis=(2, 3))

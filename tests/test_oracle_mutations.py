@@ -55,6 +55,12 @@ MUTATIONS = [
     ("threshold_additive", R, "return float(tau_base) * (1.0 + delta)", "return float(tau_base) + delta"),
     ("slice_shift_sign", S, "shift=(-int(shift_h), -int(shift_w)), axis=(2, 3))", "shift=(int(shift_h), int(shift_w)), axis=(2, 3))"),
     ("blend_shift_axes_swapped", S, "shift=(int(shift_h), int(shift_w)), axis=(2, 3))", "shift=(int(shift_w), int(shift_h)), axis=(2, 3))"),
+    ("shift_ignores_frequency", S, "moves = (step // frequency) % loop_step", "moves = step % loop_step"),
+    ("shift_loop_never_closes", S, "moves = (step // frequency) % loop_step", "moves = step // frequency"),
+    ("shift_axes_swapped", S, "return (moves * int(tile_h)) // loop_step, (moves * int(tile_w)) // loop_step",
+     "return (moves * int(tile_w)) // loop_step, (moves * int(tile_h)) // loop_step"),
+    ("shift_stride_rounded_per_move", S, "return (moves * int(tile_h)) // loop_step, (moves * int(tile_w)) // loop_step",
+     "return moves * (int(tile_h) // loop_step), moves * (int(tile_w) // loop_step)"),
     ("update_coefficients_swapped", S,
      "return float(c_latent) * np.asarray(latent, dtype=np.float64) + float(c_noise) * n",
      "return float(c_noise) * np.asarray(latent, dtype=np.float64) + float(c_latent) * n"),

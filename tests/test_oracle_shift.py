@@ -80,3 +80,56 @@ def test_fuse_and_denoise_is_the_affine_update():
     np.testing.assert_allclose(oracle.fuse_and_denoise(tiles, GO, lat, 1.0, -0.05), lat - 0.05 * n, rtol=1e-15)
     np.testing.assert_allclose(oracle.fuse_and_denoise(tiles, GO, lat, 0.9, 0.3, 1, 2),
                                0.9 * lat + 0.3 * oracle.blend_shifted(tiles, GO, 1, 2), rtol=1e-15)
+
+
+# ------------------------------------------------------------------ the shift schedule (Algorithm 1 "ShiftThisStep")
+def _golden_shift_rows():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "shift_loop16.txt")
+    return [tuple(int(v) for v in line.split()) for line in open(path) if line.strip() and not line.startswith("#")]
+
+
+def test_shift_schedule_matches_the_hand_worked_loop_of_16():
+    """Section 8 "Workloads": loop step 16 on the 160 x 90 latent tile, shifting every step."""
+    for moves, along_160, along_90 in _golden_shift_rows():
+        assert oracle.shift_schedule(moves, 90, 160, loop_step=16, frequency=1) == (along_90, along_160)
+
+
+def test_shift_schedule_frequency_holds_the_partition_between_moves():
+    """A frequency of x shifts every x steps: x consecutive steps share a position, and the loop takes 16 x steps."""
+    rows = _golden_shift_rows()
+    for freq in (1, 2, 5):
+        for step in range(0, 16 * freq + 3):
+            moves = (step // freq) % 16
+            assert oracle.shift_schedule(step, 90, 160, 16, freq) == (rows[moves][2], rows[moves][1])
+        assert oracle.shift_schedule(16 * freq, 90, 160, 16, freq) == (0, 0)
+        assert oracle.shift_schedule(freq, 90, 160, 16, freq) != oracle.shift_schedule(freq - 1, 90, 160, 16, freq)
+
+
+def test_shift_schedule_properties():
+    for th, tw, loop in ((45, 80, 16), (48, 80, 16), (3, 4, 2), (10, 10, 7), (5, 9, 1)):
+        prev = (0, 0)
+        assert oracle.shift_schedule(0, th, tw, loop) == (0, 0)
+        for s in range(1, loop):
+            dy, dx = oracle.shift_schedule(s, th, tw, loop)
+            assert 0 <= dy < th and 0 <= dx < tw
+            # every move is 1/loop of the tile, to within the one token that rounding costs
+            assert dy - prev[0] in (th // loop, -(-th // loop)) and dx - prev[1] in (tw // loop, -(-tw // loop))
+            prev = (dy, dx)
+        assert oracle.shift_schedule(loop, th, tw, loop) == (0, 0)            # the loop closes
+    with pytest.raises(ValueError):
+        oracle.shift_schedule(-1, 4, 4)
+    with pytest.raises(ValueError):
+        oracle.shift_schedule(0, 4, 4, loop_step=0)
+    with pytest.raises(ValueError):
+        oracle.shift_schedule(0, 4, 4, frequency=0)
+
+
+def test_a_whole_tile_of_shift_is_the_same_partition():
+    """Why the count of moves is taken modulo the loop step: moved by one whole tile along both directions, a
+    non-overlapping wrapping partition consists of the same windows (tile (r, c) sits where (r + 1, c + 1) sat)."""
+    c = _canvas(GP, 7)
+    for tr in range(GP.n_tile_rows):
+        for tc in range(GP.n_tile_cols):
+            moved = oracle.slice_tile_shifted(c, GP, tr, tc, GP.tile_h, GP.tile_w)
+            np.testing.assert_array_equal(moved, oracle.slice_tile(c, GP, (tr + 1) % GP.n_tile_rows, (tc + 1) % GP.n_tile_cols))
