@@ -142,6 +142,19 @@ int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const
                          float c_noise, void* latent_out, void* stream);
 
 /*
+ * Where the partition sits at a denoising step (Algorithm 1 "ShiftThisStep" / "Shift"; Section 4.2: deterministic
+ * shifts along both directions with a fixed stride; Section 8 "Workloads": loop step 16, i.e. a stride of 1/16 of the
+ * tile size, shifting every step; appendix: loop step = 1 / shift stride, a frequency of x shifts every x steps).
+ * Host only; nothing is launched.  With moves = (step / frequency) mod loop_step (integer division):
+ *     *shift_h = floor(moves * tile_h / loop_step),   *shift_w = floor(moves * tile_w / loop_step)
+ * - after loop_step moves the partition has travelled one whole tile, which for equal non-overlapping tiles on the
+ * wrapping canvas is the partition it started from.  The results are valid sg_problem.shift_h / shift_w values.
+ *   step >= 0: 0 for the first denoising step;  loop_step >= 1;  frequency >= 1 (anything else: SG_ERR_INVALID_ARG)
+ */
+int sg_shift_schedule(const sg_problem* p, int32_t step, int32_t loop_step, int32_t frequency, int32_t* shift_h,
+                      int32_t* shift_w);
+
+/*
  * SliceTile into packed form (Algorithm 1 "SliceTile"; with shift_h / shift_w the shifted, wrapping
  * partition of "Shift").  Gathers the window of tile (tile_row, tile_col) out of n_src (1..3) canvas
  * tensors into dst = [n_src][heads][T][tile_h][tile_w][d]; with q, k, v as the sources dst is the

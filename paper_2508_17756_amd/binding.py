@@ -109,6 +109,8 @@ def load_library():
     lib.sg_tile_blend.argtypes = [ctypes.POINTER(sg_problem), pp, vp, vp]
     lib.sg_tile_blend_update.restype = ctypes.c_int
     lib.sg_tile_blend_update.argtypes = [ctypes.POINTER(sg_problem), pp, vp, f32, f32, vp, vp]
+    lib.sg_shift_schedule.restype = ctypes.c_int
+    lib.sg_shift_schedule.argtypes = [ctypes.POINTER(sg_problem), i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.sg_tile_slice.restype = ctypes.c_int
     lib.sg_tile_slice.argtypes = [ctypes.POINTER(sg_problem), pp, i32, i32, i32, vp, vp]
     lib.sg_cache_gate.restype = ctypes.c_int
@@ -232,6 +234,15 @@ def sg_tile_blend_update(p, tile_out, latent_in, c_latent, c_noise, latent_out):
                                              float(c_noise), _ptr(latent_out), _stream())
     _check(st, "sg_tile_blend_update")
     return latent_out
+
+
+def sg_shift_schedule(p, step, loop_step=16, frequency=1):
+    """(shift_h, shift_w) of the partition at denoising step `step` (Algorithm 1 "ShiftThisStep" / "Shift")."""
+    dy, dx = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = load_library().sg_shift_schedule(ctypes.byref(p), int(step), int(loop_step), int(frequency), ctypes.byref(dy),
+                                          ctypes.byref(dx))
+    _check(st, "sg_shift_schedule")
+    return dy.value, dx.value
 
 
 def sg_tile_slice(p, src, tile_row, tile_col, dst):

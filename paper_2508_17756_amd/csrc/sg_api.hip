@@ -183,6 +183,21 @@ int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const
   return launch_blend(*p, tile_out, latent_out, latent_in, c_latent, c_noise, (hipStream_t)stream);
 }
 
+int sg_shift_schedule(const sg_problem* p, int32_t step, int32_t loop_step, int32_t frequency, int32_t* shift_h,
+                      int32_t* shift_w) {
+  sg_problem unshifted;
+  if (!p || !shift_h || !shift_w) return SG_ERR_INVALID_ARG;
+  unshifted = *p;                      // the schedule says where the partition goes: the caller's current shift is not an input
+  unshifted.shift_h = unshifted.shift_w = 0;
+  int st = validate(&unshifted);
+  if (st != SG_OK) return st;
+  if (step < 0 || loop_step < 1 || frequency < 1) return SG_ERR_INVALID_ARG;
+  const int64_t moves = (step / frequency) % loop_step;
+  *shift_h = (int32_t)(moves * p->tile_h / loop_step);   // < tile_h <= H
+  *shift_w = (int32_t)(moves * p->tile_w / loop_step);
+  return SG_OK;
+}
+
 int sg_tile_slice(const sg_problem* p, const void* const* src, int32_t n_src, int32_t tile_row, int32_t tile_col,
                   void* dst, void* stream) {
   int st = validate(p);

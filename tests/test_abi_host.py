@@ -148,3 +148,25 @@ def test_bench_refuses_more_than_one_gpu(repo_root):
     run = subprocess.run([sys.executable, f"{repo_root}/bench.py", "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert run.returncode != 0
     assert "one GPU" in (run.stdout + run.stderr)
+
+
+def test_shift_schedule_follows_the_oracle_and_rejects_bad_arguments():
+    """Algorithm 1 "ShiftThisStep" / "Shift" on the host: the C entry point against the oracle's schedule."""
+    import oracle
+    lib = sg.load_library()
+    for name in ("canvas2k_bf16", "canvas4k_bf16", "tiny_f32"):
+        g = CONFIGS[name]
+        p = sg.make_problem(g)
+        for loop, freq in ((16, 1), (16, 3), (7, 2), (1, 1)):
+            for step in range(0, loop * freq + 5):
+                dy, dx = sg.sg_shift_schedule(p, step, loop, freq)
+                assert (dy, dx) == oracle.shift_schedule(step, g.tile_h, g.tile_w, loop, freq)
+                q = sg.make_problem(g, shift=(dy, dx))
+                assert lib.sg_problem_validate(ctypes.byref(q)) == sg.SG_OK      # a shift the other calls accept
+    p = sg.make_problem(CONFIGS["tiny_f32"])
+    dy, dx = ctypes.c_int32(-7), ctypes.c_int32(-7)
+    for step, loop, freq in ((-1, 16, 1), (0, 0, 1), (0, 16, 0)):
+        assert lib.sg_shift_schedule(ctypes.byref(p), step, loop, freq, ctypes.byref(dy), ctypes.byref(dx)) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_shift_schedule(ctypes.byref(p), 0, 16, 1, None, ctypes.byref(dx)) == sg.SG_ERR_INVALID_ARG
+    assert lib.sg_shift_schedule(None, 0, 16, 1, ctypes.byref(dy), ctypes.byref(dx)) == sg.SG_ERR_INVALID_ARG
+    assert (dy.value, dx.value) == (-7, -7)                                       # nothing written on failure

@@ -315,3 +315,34 @@ def test_refine_step_canvas_rejected_call_gathers_nothing():
                                 torch.zeros(n, dtype=torch.uint8, device="cuda"), None, canvas=qkv)
     torch.cuda.synchronize()
     assert all(int(t.abs().sum()) == 0 for t in x[0])
+
+
+def test_canvas_steps_follow_the_shift_schedule():
+    """Algorithm 1 over six steps on a non-overlapping 2 x 2 partition with loop step 4, shifting every second step:
+    each step asks the library where the partition sits, runs the tiled step there (windows that wrap are read in
+    place) and must give the oracle's shifted attention and Fuse; after the loop the partition is back at the start."""
+    g = _geom("sched", 2, 16, 24, 8, 12, 8, 12, 2, 128, "bf16", 41)         # 2 x 2 non-overlapping tiles, N = 192
+    qkv = [randn_tensor(g.grid_shape, "bf16", g.seed + 7 * s).cuda() for s in range(3)]
+    host = [to_f64(t) for t in qkv]
+    tiles = [torch.empty(g.tile_shape, dtype=torch.bfloat16, device="cuda") for _ in range(g.n_tiles)]
+    canvas = torch.empty(g.grid_shape, dtype=torch.bfloat16, device="cuda")
+    seen = []
+    for step in range(9):
+        shift = sg.sg_shift_schedule(sg.make_problem(g), step, loop_step=4, frequency=2)
+        assert shift == oracle.shift_schedule(step, g.tile_h, g.tile_w, 4, 2)
+        seen.append(shift)
+        if step in (1, 3, 5, 7):       # one step of every position is enough
+            continue
+        p = sg.make_problem(g, shift=shift)
+        sg.sg_denoise_step_tiled(p, canvas, tiles, q=qkv[0], k=qkv[1], v=qkv[2])
+        torch.cuda.synchronize()
+        outs = []
+        for tr in range(g.n_tile_rows):
+            for tc in range(g.n_tile_cols):
+                Q, K, V = (oracle.slice_tile_shifted(t, g, tr, tc, *shift) for t in host)
+                outs.append(np.stack([oracle.attention(Q[a].reshape(-1, 128), K[a].reshape(-1, 128), V[a].reshape(-1, 128), g.scale)
+                                      for a in range(g.heads)]).reshape(g.tile_shape))
+        for t, o in zip(tiles, outs):
+            assert_close(to_f64(t), o, "bf16", f"step {step}")
+        assert_close(to_f64(canvas), oracle.blend_shifted(outs, g, *shift), "bf16", f"canvas at step {step}")
+    assert seen == [(0, 0), (0, 0), (2, 3), (2, 3), (4, 6), (4, 6), (6, 9), (6, 9), (0, 0)]
