@@ -9,6 +9,7 @@
 int main(void) {
   sg_problem p;
   size_t ws = 0;
+  int32_t dy = -1, dx = -1;
   int st;
   memset(&p, 0, sizeof p);
   p.T = 3; p.H = 16; p.W = 16;
@@ -37,6 +38,8 @@ int main(void) {
   printf("null_attention=%d\n", sg_tile_attention(&p, NULL, NULL, NULL, 0, 0, NULL, NULL));
   printf("null_blend=%d\n", sg_tile_blend(&p, NULL, NULL, NULL));
   printf("null_step=%d\n", sg_denoise_step_tiled(&p, NULL, NULL));
+  st = sg_shift_schedule(&p, 5, 4, 2, &dy, &dx);   /* step 5, loop step 4, every 2nd step: 2 moves of 10 / 4 */
+  printf("shift_status=%d\nshift_h=%d\nshift_w=%d\n", st, (int)dy, (int)dx);
   printf("status_string=%s\n", sg_status_string(SG_ERR_INVALID_ARG));
   return 0;
 }

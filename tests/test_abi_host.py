@@ -141,6 +141,7 @@ def test_plain_c_client_compiles_links_and_agrees_on_layout(repo_root, tmp_path)
     assert int(kv["workspace_status"]) == sg.SG_OK and int(kv["workspace_bytes"]) == sg.sg_workspace_bytes(20)
     assert int(kv["null_attention"]) == int(kv["null_blend"]) == int(kv["null_step"]) == sg.SG_ERR_INVALID_ARG
     assert kv["status_string"] == "invalid argument"
+    assert (int(kv["shift_status"]), int(kv["shift_h"]), int(kv["shift_w"])) == (sg.SG_OK, 5, 5)
 
 
 def test_bench_refuses_more_than_one_gpu(repo_root):
