@@ -6,6 +6,7 @@ package: only tests, the smoke check and the CPU-baseline leg of the benchmark
 may call it.
 """
 from .tile_oracle import (  # noqa: F401
+    partition_tiles,
     tile_origin,
     slice_tile,
     softmax_rows,

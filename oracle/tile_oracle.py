@@ -29,6 +29,25 @@ import numpy as np
 # --------------------------------------------------------------------------
 # Tile geometry: PartitionTiles / SliceTile (Algorithm 1, stage 2; Section 4.2)
 # --------------------------------------------------------------------------
+def partition_tiles(H, W, tile_h, tile_w, overlap_h=0, overlap_w=0):
+    """PartitionTiles: how many tiles of tile_h x tile_w tokens, neighbours sharing overlap_h /
+    overlap_w tokens, cover an H x W canvas exactly -> (n_tile_rows, n_tile_cols, stride_h,
+    stride_w).  The paper's partition is the case overlap = 0 (Section 4.2: non-overlapping
+    tiles).  Tiles are placed at multiples of stride = tile - overlap; the last one must end
+    at the canvas edge, otherwise the canvas has no such partition (ValueError).
+    """
+    out = []
+    for extent, tile, overlap in ((int(H), int(tile_h), int(overlap_h)), (int(W), int(tile_w), int(overlap_w))):
+        if tile < 1 or extent < tile or not (0 <= overlap < tile):
+            raise ValueError("need 1 <= tile <= extent and 0 <= overlap < tile")
+        stride = tile - overlap
+        origins = list(range(0, extent - tile + 1, stride))
+        if origins[-1] + tile != extent:
+            raise ValueError("tiles of %d with overlap %d do not end at %d" % (tile, overlap, extent))
+        out.append((len(origins), stride))
+    return out[0][0], out[1][0], out[0][1], out[1][1]
+
+
 def tile_origin(g, tile_row, tile_col):
     """Top-left grid token (row, col) of tile (tile_row, tile_col)."""
     if not (0 <= tile_row < g.n_tile_rows and 0 <= tile_col < g.n_tile_cols):

@@ -156,3 +156,36 @@ def test_paper_tile_counts(repo_root):
         origins = [oracle.tile_origin(g, r, c) for r in range(g.n_tile_rows) for c in range(g.n_tile_cols)]
         assert len(set(origins)) == n
         assert max(o[0] for o in origins) + th == H and max(o[1] for o in origins) + tw == W
+
+
+def test_partition_tiles_gives_the_paper_counts_and_the_benchmark_tilings(repo_root):
+    """PartitionTiles against what is fixed elsewhere: the paper's 4 and 9 tiles (Section 8 "Workloads"), the five
+    benchmark geometries (their tile counts and strides are inputs there, not derived), and coverage by brute force."""
+    from synthetic import CONFIGS
+    for line in open(f"{repo_root}/tests/golden/tile_counts.txt"):
+        if line.startswith("#") or not line.strip():
+            continue
+        H, W, th, tw, n = map(int, line.split())
+        nr, nc, sh, sw = oracle.partition_tiles(H, W, th, tw)
+        assert nr * nc == n and (sh, sw) == (th, tw)
+    for g in CONFIGS.values():
+        got = oracle.partition_tiles(g.H, g.W, g.tile_h, g.tile_w, g.tile_h - g.stride_h if g.n_tile_rows > 1 else 0,
+                                     g.tile_w - g.stride_w if g.n_tile_cols > 1 else 0)
+        assert got[:2] == (g.n_tile_rows, g.n_tile_cols)
+        if g.n_tile_rows > 1:
+            assert got[2] == g.stride_h
+        if g.n_tile_cols > 1:
+            assert got[3] == g.stride_w
+    # brute force: every row and column is covered, no tile sticks out, neighbours share exactly the overlap
+    for H, th, oh in ((16, 10, 4), (90, 48, 27), (135, 45, 15), (12, 4, 0), (7, 7, 0), (9, 5, 3)):
+        nr, _, sh, _ = oracle.partition_tiles(H, 8, th, 8, oh, 0)
+        cover = np.zeros(H, dtype=int)
+        for r in range(nr):
+            assert r * sh + th <= H
+            cover[r * sh:r * sh + th] += 1
+        assert cover.min() >= 1 and (nr - 1) * sh + th == H
+        if nr > 1:
+            assert th - sh == oh
+    for bad in ((10, 8, 4, 8, 0, 0), (16, 8, 10, 8, 3, 0), (16, 8, 20, 8, 0, 0), (16, 8, 4, 8, 4, 0), (16, 8, 0, 8, 0, 0)):
+        with pytest.raises(ValueError):
+            oracle.partition_tiles(*bad)

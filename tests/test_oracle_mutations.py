@@ -17,6 +17,9 @@ MUTATIONS = [
     ("scores_against_values", A, "s = float(scale) * (q_rows @ K.T)", "s = float(scale) * (q_rows @ V.T)"),
     ("scale_dropped", A, "s = float(scale) * (q_rows @ K.T)", "s = (q_rows @ K.T)"),
     ("softmax_over_queries", A, "return e / e.sum(axis=1, keepdims=True)", "return e / e.sum(axis=0, keepdims=True)"),
+    ("partition_stride_ignores_overlap", A, "        stride = tile - overlap\n", "        stride = tile\n"),
+    ("partition_accepts_a_gap_at_the_edge", A, "        if origins[-1] + tile != extent:", "        if origins[-1] + tile > extent:"),
+    ("partition_drops_the_last_tile", A, "origins = list(range(0, extent - tile + 1, stride))", "origins = list(range(0, extent - tile, stride)) or [0]"),
     ("ramp_i_not_i_plus_1", B, "np.minimum((i + 1.0) / (o + 1.0), (L - i) / (o + 1.0))",
      "np.minimum(i / (o + 1.0), (L - i) / (o + 1.0))"),
     ("ramp_falling_edge_off_by_one", B, "(L - i) / (o + 1.0)))", "(L - i - 1.0) / (o + 1.0)))"),
