@@ -142,6 +142,16 @@ int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const
                          float c_noise, void* latent_out, void* stream);
 
 /*
+ * PartitionTiles (Algorithm 1, stage 2; Section 4.2: the canvas is cut along height and width only).  Host only.
+ * Fills p->tile_h, tile_w, stride_h, stride_w, n_tile_rows, n_tile_cols for tiles of tile_h x tile_w tokens whose
+ * neighbours share overlap_h / overlap_w tokens (0 = the paper's non-overlapping tiles) on the canvas p->H x p->W,
+ * which must be set; the other fields of *p are neither read nor written.  Tiles sit at multiples of
+ * stride = tile - overlap and the last one has to end at the canvas edge: if no such partition exists, or more than
+ * SG_MAX_TILES tiles result, nothing is written (SG_ERR_INVALID_ARG / SG_ERR_UNSUPPORTED).
+ */
+int sg_partition_tiles(sg_problem* p, int32_t tile_h, int32_t tile_w, int32_t overlap_h, int32_t overlap_w);
+
+/*
  * Where the partition sits at a denoising step (Algorithm 1 "ShiftThisStep" / "Shift"; Section 4.2: deterministic
  * shifts along both directions with a fixed stride; Section 8 "Workloads": loop step 16, i.e. a stride of 1/16 of the
  * tile size, shifting every step; appendix: loop step = 1 / shift stride, a frequency of x shifts every x steps).

@@ -6,6 +6,6 @@ from .binding import (  # noqa: F401
     sg_tile_attention, sg_tile_blend, sg_cache_gate, sg_denoise_step_tiled,
     sg_gain_state, sg_gain_step_io, GainState, sg_gain_gate, sg_gain_refresh, sg_denoise_step_gain,
     SG_REGION_MAXMIN, SG_REGION_TOPSELECT, sg_tile_std, sg_region_thresholds,
-    sg_tile_blend_update, sg_tile_slice, sg_shift_schedule, sg_region_control, sg_scheduler_update,
+    sg_tile_blend_update, sg_tile_slice, sg_shift_schedule, sg_partition_tiles, sg_region_control, sg_scheduler_update,
     sg_cache_gate_static, SG_STATIC_GATE_MAX_TILES, sg_tile_similarity,
 )

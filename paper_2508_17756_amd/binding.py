@@ -109,6 +109,8 @@ def load_library():
     lib.sg_tile_blend.argtypes = [ctypes.POINTER(sg_problem), pp, vp, vp]
     lib.sg_tile_blend_update.restype = ctypes.c_int
     lib.sg_tile_blend_update.argtypes = [ctypes.POINTER(sg_problem), pp, vp, f32, f32, vp, vp]
+    lib.sg_partition_tiles.restype = ctypes.c_int
+    lib.sg_partition_tiles.argtypes = [ctypes.POINTER(sg_problem), i32, i32, i32, i32]
     lib.sg_shift_schedule.restype = ctypes.c_int
     lib.sg_shift_schedule.argtypes = [ctypes.POINTER(sg_problem), i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.sg_tile_slice.restype = ctypes.c_int
@@ -234,6 +236,13 @@ def sg_tile_blend_update(p, tile_out, latent_in, c_latent, c_noise, latent_out):
                                              float(c_noise), _ptr(latent_out), _stream())
     _check(st, "sg_tile_blend_update")
     return latent_out
+
+
+def sg_partition_tiles(p, tile_h, tile_w, overlap_h=0, overlap_w=0):
+    """PartitionTiles: fills the tiling fields of p for its canvas p.H x p.W; returns p."""
+    _check(load_library().sg_partition_tiles(ctypes.byref(p), int(tile_h), int(tile_w), int(overlap_h), int(overlap_w)),
+           "sg_partition_tiles")
+    return p
 
 
 def sg_shift_schedule(p, step, loop_step=16, frequency=1):

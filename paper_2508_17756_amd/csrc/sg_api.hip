@@ -183,6 +183,23 @@ int sg_tile_blend_update(const sg_problem* p, const void* const* tile_out, const
   return launch_blend(*p, tile_out, latent_out, latent_in, c_latent, c_noise, (hipStream_t)stream);
 }
 
+int sg_partition_tiles(sg_problem* p, int32_t tile_h, int32_t tile_w, int32_t overlap_h, int32_t overlap_w) {
+  if (!p || p->H <= 0 || p->W <= 0) return SG_ERR_INVALID_ARG;
+  const int32_t extent[2] = {p->H, p->W}, tile[2] = {tile_h, tile_w}, overlap[2] = {overlap_h, overlap_w};
+  int32_t count[2], stride[2];
+  for (int a = 0; a < 2; ++a) {
+    if (tile[a] < 1 || tile[a] > extent[a] || overlap[a] < 0 || overlap[a] >= tile[a]) return SG_ERR_INVALID_ARG;
+    stride[a] = tile[a] - overlap[a];
+    if ((extent[a] - tile[a]) % stride[a] != 0) return SG_ERR_INVALID_ARG;   // the last tile would not end at the edge
+    count[a] = (extent[a] - tile[a]) / stride[a] + 1;
+  }
+  if ((int64_t)count[0] * count[1] > SG_MAX_TILES) return SG_ERR_UNSUPPORTED;
+  p->tile_h = tile_h; p->tile_w = tile_w;
+  p->stride_h = stride[0]; p->stride_w = stride[1];
+  p->n_tile_rows = count[0]; p->n_tile_cols = count[1];
+  return SG_OK;
+}
+
 int sg_shift_schedule(const sg_problem* p, int32_t step, int32_t loop_step, int32_t frequency, int32_t* shift_h,
                       int32_t* shift_w) {
   sg_problem unshifted;

@@ -171,3 +171,37 @@ def test_shift_schedule_follows_the_oracle_and_rejects_bad_arguments():
     assert lib.sg_shift_schedule(ctypes.byref(p), 0, 16, 1, None, ctypes.byref(dx)) == sg.SG_ERR_INVALID_ARG
     assert lib.sg_shift_schedule(None, 0, 16, 1, ctypes.byref(dy), ctypes.byref(dx)) == sg.SG_ERR_INVALID_ARG
     assert (dy.value, dx.value) == (-7, -7)                                       # nothing written on failure
+
+
+def test_partition_tiles_follows_the_oracle_and_leaves_the_problem_alone_on_failure():
+    """Algorithm 1 "PartitionTiles" on the host: the C entry point against the oracle, over the benchmark geometries
+    and a sweep of small canvases, including every combination that has no exact partition."""
+    import oracle
+    lib = sg.load_library()
+    for g in CONFIGS.values():
+        p = sg.make_problem(g)
+        want = (p.n_tile_rows, p.n_tile_cols, p.stride_h, p.stride_w)
+        p.n_tile_rows = p.n_tile_cols = p.stride_h = p.stride_w = p.tile_h = p.tile_w = 0
+        sg.sg_partition_tiles(p, g.tile_h, g.tile_w, g.tile_h - g.stride_h if g.n_tile_rows > 1 else 0,
+                              g.tile_w - g.stride_w if g.n_tile_cols > 1 else 0)
+        got = (p.n_tile_rows, p.n_tile_cols, p.stride_h, p.stride_w)
+        if g.n_tile_rows > 1 and g.n_tile_cols > 1:
+            assert got == want
+        assert lib.sg_problem_validate(ctypes.byref(p)) == sg.SG_OK
+    p = sg.make_problem(CONFIGS["tiny_f32"])
+    for H in (7, 12, 16):
+        for th in range(0, H + 2):
+            for oh in range(-1, th + 1):
+                p.H, p.W = H, 24
+                before = bytes(p)
+                st = lib.sg_partition_tiles(ctypes.byref(p), th, 8, oh, 0)
+                try:
+                    nr, nc, sh, sw = oracle.partition_tiles(H, 24, th, 8, oh, 0)
+                except ValueError:
+                    assert st == sg.SG_ERR_INVALID_ARG and bytes(p) == before, (H, th, oh)
+                else:
+                    assert st == sg.SG_OK and (p.n_tile_rows, p.n_tile_cols, p.stride_h, p.stride_w) == (nr, nc, sh, sw)
+    p.H, p.W = 300, 300
+    before = bytes(p)
+    assert lib.sg_partition_tiles(ctypes.byref(p), 10, 10, 0, 0) == sg.SG_ERR_UNSUPPORTED and bytes(p) == before   # 900 tiles
+    assert lib.sg_partition_tiles(None, 10, 10, 0, 0) == sg.SG_ERR_INVALID_ARG
